@@ -1,0 +1,385 @@
+/*
+ * nz_oracle.c -- plain CPU oracle for the multi-rail allreduce arithmetic.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Nothing in the product library may include, link
+ * or call this file; it exists so that tests, the smoke check and the CPU
+ * baseline leg of the benchmark have an independent statement of what the
+ * GPU path must compute.  It shares no code, header, table or helper with the
+ * HIP sources.
+ *
+ * What it states (Nezha, arXiv 2405.17870):
+ *   - Sec. 3.4 / 3.5 / 4.2: the Load Balancer hands every member network one
+ *     contiguous (ptr, data_length) slice of the message; the slices'
+ *     proportions alpha sum to one (Sec. 4.3, text under Eq. 5).
+ *   - Sec. 2.1.1, Eq. 1: a ring allreduce over N workers moves
+ *     2(N-1) * M/N per worker: N-1 reduce-scatter steps and N-1 allgather
+ *     steps over N pieces of the message.
+ *   - Sec. 4.2: the "data aggregation (computation)" phase is the elementwise
+ *     sum of the workers' gradients; every worker ends with the same sums.
+ *   - Sec. 3.2: a rail's slice is staged from the user buffer (UnboundBuffer)
+ *     into a contiguous per-rail Buffer and the result is returned.
+ *
+ * Everything is written as the definition or as the literal step sequence:
+ * no blocking, no vectorisation, no reordering.  Floating-point definitional
+ * sums are taken in fp64, left to right over the node index.
+ *
+ * Every function here is pinned by tests/test_oracle_*.py against closed
+ * forms, brute force, hand-worked cases and library routines.
+ */
+#include <stddef.h>
+#include <stdint.h>
+#include <string.h>
+#include <math.h>
+
+#define ORC_OK 0
+#define ORC_BAD 1
+
+enum { ORC_F32 = 0, ORC_BF16 = 1, ORC_F16 = 2, ORC_I32 = 3 };
+
+static int elem_bytes_of(int dtype)
+{
+    switch (dtype) {
+    case ORC_F32: return 4;
+    case ORC_I32: return 4;
+    case ORC_BF16: return 2;
+    case ORC_F16: return 2;
+    default: return 0;
+    }
+}
+
+/* ---------------------------------------------------------------------- */
+/* 16-bit float formats (IEEE binary16 and bfloat16), by their definitions */
+/* ---------------------------------------------------------------------- */
+
+static uint32_t f32_bits(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+static float bits_f32(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
+
+/* bfloat16 is the upper half of a binary32: widening appends 16 zero bits. */
+float orc_bf16_to_f32(uint16_t h) { return bits_f32((uint32_t)h << 16); }
+
+/* binary32 -> bfloat16, round to nearest, ties to even; NaN stays a quiet NaN. */
+uint16_t orc_f32_to_bf16(float f)
+{
+    uint32_t u = f32_bits(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u)            /* NaN */
+        return (uint16_t)((u >> 16) | 0x0040u);
+    uint32_t low = u & 0xffffu;                      /* the 16 dropped bits   */
+    uint32_t top = u >> 16;
+    if (low > 0x8000u || (low == 0x8000u && (top & 1u)))
+        top += 1u;              /* carries into the exponent (and to Inf) correctly */
+    return (uint16_t)top;
+}
+
+/* IEEE binary16 -> binary32 (exact). */
+float orc_f16_to_f32(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+    int exp = (h >> 10) & 0x1f;
+    uint32_t man = h & 0x3ffu;
+    if (exp == 0x1f)
+        return bits_f32(sign | 0x7f800000u | (man << 13));
+    if (exp == 0) {
+        /* zero or subnormal: value = man * 2^-24 */
+        float v = ldexpf((float)man, -24);
+        return sign ? -v : v;
+    }
+    return bits_f32(sign | ((uint32_t)(exp - 15 + 127) << 23) | (man << 13));
+}
+
+/* binary32 -> IEEE binary16, round to nearest, ties to even. */
+uint16_t orc_f32_to_f16(float f)
+{
+    uint32_t u = f32_bits(f);
+    uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+    uint32_t a = u & 0x7fffffffu;
+    if (a > 0x7f800000u)
+        return (uint16_t)(sign | 0x7e00u | ((a >> 13) & 0x3ffu));   /* quiet NaN */
+    if (a == 0x7f800000u)
+        return (uint16_t)(sign | 0x7c00u);
+    /* |f| as an exact multiple of 2^-24 would overflow for large values, so
+       split by magnitude. */
+    float af = bits_f32(a);
+    if (af >= 65520.0f)                   /* rounds to infinity (max half 65504, ulp 32) */
+        return (uint16_t)(sign | 0x7c00u);
+    if (af < 6.103515625e-05f) {          /* below 2^-14: subnormal half, spacing 2^-24 */
+        /* nearbyintf in the default rounding mode is round-half-even; the
+           scaling by 2^24 is exact. */
+        float q = nearbyintf(ldexpf(af, 24));
+        return (uint16_t)(sign | (uint16_t)q);     /* q == 1024 lands on the smallest normal */
+    }
+    int e = (int)(a >> 23) - 127;                  /* -14 .. 15 */
+    uint32_t man = a & 0x7fffffu;
+    uint32_t keep = man >> 13;
+    uint32_t low = man & 0x1fffu;
+    uint32_t h = ((uint32_t)(e + 15) << 10) | keep;
+    if (low > 0x1000u || (low == 0x1000u && (keep & 1u)))
+        h += 1u;                                   /* may carry into the exponent */
+    return (uint16_t)(sign | h);
+}
+
+/* ---------------------------------------------------------------------- */
+/* Rail partition (Sec. 3.5 Load Balancer, Sec. 4.3 proportions)           */
+/* ---------------------------------------------------------------------- */
+
+/*
+ * Split [0, n) into n_rails contiguous ranges, in rail order, with lengths
+ * proportional to the integer weights w[].  Every interior boundary is the
+ * proportional point n * (w_0 + ... + w_{k-1}) / W rounded DOWN to a
+ * multiple of align_elems; b[0] = 0 and b[n_rails] = n, so the last rail
+ * takes whatever the rounding leaves.  A rail of weight zero is given nothing
+ * (that is how "all data on the best rail", Eq. 4, and a failed rail,
+ * Sec. 4.4, are expressed): once the weights before a boundary already add
+ * up to W, that boundary is n itself, so the remainder goes to the last rail
+ * of non-zero weight.
+ */
+int orc_rail_partition(uint64_t n, uint64_t align_elems, const uint32_t *w,
+                       uint32_t n_rails, uint64_t *b)
+{
+    if (!w || !b || n_rails == 0 || align_elems == 0) return ORC_BAD;
+    uint64_t W = 0;
+    for (uint32_t k = 0; k < n_rails; ++k) W += w[k];
+    if (W == 0) return ORC_BAD;
+    b[0] = 0;
+    uint64_t P = 0;
+    for (uint32_t k = 1; k < n_rails; ++k) {
+        P += w[k - 1];
+        if (P == W) { b[k] = n; continue; }
+        unsigned __int128 num = (unsigned __int128)n * P;
+        unsigned __int128 den = (unsigned __int128)W * align_elems;
+        b[k] = (uint64_t)(num / den) * align_elems;
+    }
+    b[n_rails] = n;
+    return ORC_OK;
+}
+
+/* ---------------------------------------------------------------------- */
+/* Ring segments (Eq. 1: N pieces of M/N)                                  */
+/* ---------------------------------------------------------------------- */
+
+/*
+ * Cut every rail range [b[k], b[k+1]) into n_nodes consecutive segments whose
+ * lengths differ by at most one element, the longer ones first.
+ * seg is [n_rails][n_nodes + 1]: segment j of rail k is
+ * [seg[k][j], seg[k][j+1]).
+ */
+int orc_segment_map(const uint64_t *b, uint32_t n_rails, uint32_t n_nodes,
+                    uint64_t *seg)
+{
+    if (!b || !seg || n_rails == 0 || n_nodes == 0) return ORC_BAD;
+    for (uint32_t k = 0; k < n_rails; ++k) {
+        if (b[k + 1] < b[k]) return ORC_BAD;
+        uint64_t L = b[k + 1] - b[k];
+        uint64_t q = L / n_nodes, r = L % n_nodes;
+        uint64_t *row = seg + (size_t)k * (n_nodes + 1);
+        row[0] = b[k];
+        for (uint32_t j = 0; j < n_nodes; ++j)
+            row[j + 1] = row[j] + q + (j < r ? 1u : 0u);
+    }
+    return ORC_OK;
+}
+
+/* ---------------------------------------------------------------------- */
+/* Definitional allreduce: out[x] = sum over nodes of in[i][x] (Sec. 4.2)  */
+/* ---------------------------------------------------------------------- */
+
+/*
+ * Floating-point inputs: each element is widened exactly to fp64 and the N
+ * values are added left to right in fp64.  sum[x] receives the total and
+ * abssum[x] (may be NULL) the sum of magnitudes, which scales the tolerance.
+ */
+int orc_sum_float(int dtype, const void *const *in, uint32_t n_nodes,
+                  uint64_t n, double *sum, double *abssum)
+{
+    if (!in || !sum || n_nodes == 0) return ORC_BAD;
+    if (dtype != ORC_F32 && dtype != ORC_BF16 && dtype != ORC_F16) return ORC_BAD;
+#pragma omp parallel for schedule(static)
+    for (uint64_t x = 0; x < n; ++x) {
+        double s = 0.0, a = 0.0;
+        for (uint32_t i = 0; i < n_nodes; ++i) {
+            double v;
+            if (dtype == ORC_F32)
+                v = (double)((const float *)in[i])[x];
+            else if (dtype == ORC_BF16)
+                v = (double)orc_bf16_to_f32(((const uint16_t *)in[i])[x]);
+            else
+                v = (double)orc_f16_to_f32(((const uint16_t *)in[i])[x]);
+            if (i == 0) s = v; else s += v;    /* no "+0.0" in front: keeps -0 */
+            a += fabs(v);
+        }
+        sum[x] = s;
+        if (abssum) abssum[x] = a;
+    }
+    return ORC_OK;
+}
+
+/* int32 inputs: two's-complement wrapping sum (computed in uint32). */
+int orc_sum_i32(const void *const *in, uint32_t n_nodes, uint64_t n, int32_t *out)
+{
+    if (!in || !out || n_nodes == 0) return ORC_BAD;
+#pragma omp parallel for schedule(static)
+    for (uint64_t x = 0; x < n; ++x) {
+        uint32_t s = 0;
+        for (uint32_t i = 0; i < n_nodes; ++i)
+            s += ((const uint32_t *)in[i])[x];
+        out[x] = (int32_t)s;
+    }
+    return ORC_OK;
+}
+
+/*
+ * The value a 16-bit-float output must be compared with: the fp64 sum rounded
+ * once to fp32 (the accumulator precision) and then once to the storage type.
+ */
+int orc_round_to_storage(int dtype, const double *sum, uint64_t n, void *out)
+{
+    if (!sum || !out) return ORC_BAD;
+    for (uint64_t x = 0; x < n; ++x) {
+        float f = (float)sum[x];
+        if (dtype == ORC_F32) ((float *)out)[x] = f;
+        else if (dtype == ORC_BF16) ((uint16_t *)out)[x] = orc_f32_to_bf16(f);
+        else if (dtype == ORC_F16) ((uint16_t *)out)[x] = orc_f32_to_f16(f);
+        else return ORC_BAD;
+    }
+    return ORC_OK;
+}
+
+/* ---------------------------------------------------------------------- */
+/* Step-by-step ring allreduce (Eq. 1)                                     */
+/* ---------------------------------------------------------------------- */
+
+static void add_into(int dtype, void *dst, const void *src, uint64_t off, uint64_t len)
+{
+    /* dst[off..off+len) = storage( fp32(src) + fp32(dst) ); the received
+       partial is the left operand.  int32 wraps. */
+    for (uint64_t x = off; x < off + len; ++x) {
+        switch (dtype) {
+        case ORC_F32: {
+            volatile float s = ((const float *)src)[x] + ((float *)dst)[x];
+            ((float *)dst)[x] = s;
+            break;
+        }
+        case ORC_I32:
+            ((uint32_t *)dst)[x] = ((const uint32_t *)src)[x] + ((uint32_t *)dst)[x];
+            break;
+        case ORC_BF16: {
+            volatile float s = orc_bf16_to_f32(((const uint16_t *)src)[x]) +
+                               orc_bf16_to_f32(((uint16_t *)dst)[x]);
+            ((uint16_t *)dst)[x] = orc_f32_to_bf16(s);
+            break;
+        }
+        case ORC_F16: {
+            volatile float s = orc_f16_to_f32(((const uint16_t *)src)[x]) +
+                               orc_f16_to_f32(((uint16_t *)dst)[x]);
+            ((uint16_t *)dst)[x] = orc_f32_to_f16(s);
+            break;
+        }
+        }
+    }
+}
+
+/*
+ * Literal emulation of a ring allreduce run independently on every rail.
+ *
+ * buf[i] is node i's private buffer of n elements; on entry it holds node i's
+ * gradients, on exit the allreduced result.  Node r always sends to node
+ * (r+1) mod N.  In reduce-scatter step s (s = 0 .. N-2) it sends segment
+ * (r - s) mod N of every rail and the receiver adds it into its own copy,
+ * storing the partial in the storage type; after the last such step node r
+ * holds the complete segment (r + 1) mod N.  In allgather step s it sends
+ * segment (r + 1 - s) mod N and the receiver overwrites its copy.
+ *
+ * All sends of one step happen "at once": a step's sends are taken from the
+ * state at the start of the step.  No segment is both sent and received by
+ * one node in the same step, so processing the nodes one after another is
+ * the same thing.
+ *
+ * stop_after_reduce_scatter != 0 returns after the first N-1 steps.
+ * sent_bytes[i] (may be NULL) is incremented by what node i puts on the wire.
+ */
+int orc_ring_allreduce(int dtype, void *const *buf, uint32_t n_nodes, uint64_t n,
+                       const uint64_t *seg, uint32_t n_rails,
+                       int stop_after_reduce_scatter, uint64_t *sent_bytes)
+{
+    int e = elem_bytes_of(dtype);
+    if (!buf || !seg || n_nodes == 0 || n_rails == 0 || e == 0) return ORC_BAD;
+    (void)n;
+    const uint32_t N = n_nodes;
+    for (uint32_t s = 0; s + 1 < N; ++s) {
+        for (uint32_t k = 0; k < n_rails; ++k) {
+            const uint64_t *row = seg + (size_t)k * (N + 1);
+            for (uint32_t r = 0; r < N; ++r) {
+                uint32_t j = (r + N - s % N) % N;
+                uint32_t d = (r + 1) % N;
+                uint64_t off = row[j], len = row[j + 1] - row[j];
+                add_into(dtype, buf[d], buf[r], off, len);
+                if (sent_bytes) sent_bytes[r] += len * (uint64_t)e;
+            }
+        }
+    }
+    if (stop_after_reduce_scatter) return ORC_OK;
+    for (uint32_t s = 0; s + 1 < N; ++s) {
+        for (uint32_t k = 0; k < n_rails; ++k) {
+            const uint64_t *row = seg + (size_t)k * (N + 1);
+            for (uint32_t r = 0; r < N; ++r) {
+                uint32_t j = (r + 1 + N - s % N) % N;
+                uint32_t d = (r + 1) % N;
+                uint64_t off = row[j], len = row[j + 1] - row[j];
+                memcpy((char *)buf[d] + off * e, (const char *)buf[r] + off * e, len * e);
+                if (sent_bytes) sent_bytes[r] += len * (uint64_t)e;
+            }
+        }
+    }
+    return ORC_OK;
+}
+
+/* ---------------------------------------------------------------------- */
+/* Pack / unpack (Sec. 3.2: UnboundBuffer <-> per-rail Buffer)             */
+/* ---------------------------------------------------------------------- */
+
+/*
+ * Concatenate the listed segments of one rail, in list order and without
+ * padding, from node_buf into send_buf.  Returns the byte count through
+ * packed_bytes.  seg is the table of orc_segment_map.
+ */
+int orc_pack(const void *node_buf, const uint64_t *seg, uint32_t n_nodes,
+             uint32_t rail, const uint32_t *seg_ids, uint32_t n_segs,
+             uint32_t elem_bytes, void *send_buf, uint64_t *packed_bytes)
+{
+    if (!node_buf || !seg || !send_buf || (!seg_ids && n_segs)) return ORC_BAD;
+    const uint64_t *row = seg + (size_t)rail * (n_nodes + 1);
+    uint64_t pos = 0;
+    for (uint32_t i = 0; i < n_segs; ++i) {
+        uint32_t j = seg_ids[i];
+        if (j >= n_nodes) return ORC_BAD;
+        uint64_t bytes = (row[j + 1] - row[j]) * elem_bytes;
+        memcpy((char *)send_buf + pos, (const char *)node_buf + row[j] * elem_bytes, bytes);
+        pos += bytes;
+    }
+    if (packed_bytes) *packed_bytes = pos;
+    return ORC_OK;
+}
+
+/* Inverse of orc_pack: scatter send_buf back into the listed segments. */
+int orc_unpack(const void *send_buf, const uint64_t *seg, uint32_t n_nodes,
+               uint32_t rail, const uint32_t *seg_ids, uint32_t n_segs,
+               uint32_t elem_bytes, void *node_buf)
+{
+    if (!node_buf || !seg || !send_buf || (!seg_ids && n_segs)) return ORC_BAD;
+    const uint64_t *row = seg + (size_t)rail * (n_nodes + 1);
+    uint64_t pos = 0;
+    for (uint32_t i = 0; i < n_segs; ++i) {
+        uint32_t j = seg_ids[i];
+        if (j >= n_nodes) return ORC_BAD;
+        uint64_t bytes = (row[j + 1] - row[j]) * elem_bytes;
+        memcpy((char *)node_buf + row[j] * elem_bytes, (const char *)send_buf + pos, bytes);
+        pos += bytes;
+    }
+    return ORC_OK;
+}
+
+#ifdef _OPENMP
+#include <omp.h>
+int orc_threads(void) { return omp_get_max_threads(); }
+#else
+int orc_threads(void) { return 1; }
+#endif
