@@ -1,0 +1,164 @@
+/*
+ * nezha_sim.h -- C ABI of the MI355X (gfx950) reduction engine of a multi-rail
+ * allreduce, after Nezha (arXiv 2405.17870).
+ *
+ * The message of one allreduce is split across rails (member networks) into
+ * contiguous slices, each rail allreduces its slice over the N nodes with a
+ * ring, and the arithmetic of that -- the sum of the nodes' gradient buffers --
+ * is what this library executes on one GPU, with all N simulated nodes'
+ * buffers resident in device memory.  No network transport is involved.
+ *
+ * Conventions for every entry point
+ *   - Return value: nz_status.  Nothing is thrown, the process is never
+ *     aborted.  All validation happens before any GPU work is enqueued: on a
+ *     status other than NZ_OK nothing was launched and no output was written.
+ *   - "host" pointers are ordinary process memory, read (or written) before
+ *     the call returns; the caller may free them immediately afterwards.
+ *   - "device" pointers are HIP device memory owned by the caller.  The
+ *     library never allocates, frees or returns device memory.  Device
+ *     buffers must stay alive until `stream` has run past the call's work.
+ *   - `stream` is a hipStream_t passed as void*; NULL is the default stream.
+ *     GPU work is asynchronous with respect to the host.
+ *   - Every device buffer base must be aligned to 256 bytes
+ *     (NZ_ERR_ALIGNMENT otherwise); together with the 256-byte alignment of
+ *     rail boundaries this makes every rail slice start on a 256-byte address.
+ *   - Limits: n_nodes <= NZ_MAX_NODES, n_rails <= NZ_MAX_RAILS
+ *     (NZ_ERR_UNSUPPORTED beyond them).
+ *   - Entry points are re-entrant; concurrent calls must not share output
+ *     buffers.  Results are bitwise reproducible.
+ */
+#ifndef NEZHA_SIM_H
+#define NEZHA_SIM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define NZ_MAX_NODES 128u
+#define NZ_MAX_RAILS 8u
+#define NZ_RAIL_ALIGN_BYTES 256u
+
+typedef enum {
+    NZ_OK = 0,
+    NZ_ERR_INVALID_ARG = 1, /* null pointer, zero count, zero weight sum, bad enum, overflow */
+    NZ_ERR_ALIGNMENT = 2,   /* a device buffer base is not 256-byte aligned               */
+    NZ_ERR_UNSUPPORTED = 3, /* over a limit, or buffers overlap in a way not allowed      */
+    NZ_ERR_CAPACITY = 4,    /* a destination buffer is too small                          */
+    NZ_ERR_HIP = 5          /* the HIP runtime reported an error (see nz_last_hip_error)  */
+} nz_status;
+
+typedef enum { NZ_F32 = 0, NZ_BF16 = 1, NZ_F16 = 2, NZ_I32 = 3 } nz_dtype;
+
+typedef enum { NZ_RING_STEPWISE = 0, NZ_FUSED = 1 } nz_mode;
+
+/* Static text for a status code. */
+const char *nz_status_str(nz_status s);
+
+/* Text of the last HIP error seen by the calling thread ("" if none). */
+const char *nz_last_hip_error(void);
+
+/* Size in bytes of one element of `dtype`, 0 for an unknown dtype. */
+uint32_t nz_dtype_bytes(nz_dtype dtype);
+
+/*
+ * Rail partition.  (Sec. 3.4: each network is handed one (ptr, data_length)
+ * slice; Sec. 3.5: the Load Balancer derives each rail's pointer from its data
+ * volume; Sec. 4.3, under Eq. 5: the proportions sum to one.)
+ *
+ * Splits [0, n_elems) into n_rails contiguous ranges, in rail order, with
+ * lengths proportional to the integer weights ratios[k] (host, n_rails
+ * entries, sum > 0).  rail_off (host, caller-owned, n_rails + 1 entries)
+ * receives the boundaries in elements: rail k is [rail_off[k], rail_off[k+1]).
+ * rail_off[0] = 0, rail_off[n_rails] = n_elems; an interior boundary is the
+ * proportional point n_elems * (ratios[0] + .. + ratios[k-1]) / sum, rounded
+ * down to a multiple of 256 bytes; a rail of weight zero gets an empty range
+ * (a boundary preceded by the whole weight sum is n_elems).  All arithmetic
+ * is exact integer arithmetic.  elem_bytes must be 2 or 4.  Pure host
+ * function, no GPU involved.
+ */
+nz_status nz_rail_partition(uint64_t n_elems, uint32_t elem_bytes, const uint32_t *ratios,
+                            uint32_t n_rails, uint64_t *rail_off);
+
+/* The same with a caller-chosen alignment (a positive multiple of elem_bytes). */
+nz_status nz_rail_partition_ex(uint64_t n_elems, uint32_t elem_bytes, uint32_t align_bytes,
+                               const uint32_t *ratios, uint32_t n_rails, uint64_t *rail_off);
+
+/*
+ * Ring segments.  (Sec. 2.1.1, Eq. 1: a ring allreduce over N workers handles
+ * the message in N pieces of M/N.)
+ *
+ * Cuts every rail range into n_nodes consecutive segments whose lengths differ
+ * by at most one element, longer ones first, with no alignment of their own.
+ * rail_off: host, n_rails + 1 non-decreasing entries.  seg_off: host,
+ * caller-owned, [n_rails][n_nodes + 1] row-major; segment j of rail k is
+ * [seg_off[k][j], seg_off[k][j+1]).  Pure host function.
+ */
+nz_status nz_segment_map(const uint64_t *rail_off, uint32_t n_rails, uint32_t n_nodes,
+                         uint64_t *seg_off);
+
+/*
+ * Allreduce (sum) of n_nodes gradient buffers, every rail in the same launch.
+ * (Sec. 4.2: the aggregation phase of the allreduce; Sec. 2.1.1, Eq. 1: the
+ * ring schedule; Sec. 4.1: rails work on disjoint slices concurrently.)
+ *
+ * node_bufs: host array of n_nodes device pointers, each n_elems elements of
+ * `dtype`: node i's gradients.  out_bufs: host array of n_nodes device
+ * pointers receiving node i's result; on completion every out buffer holds,
+ * for every element x, the sum over i of node_bufs[i][x].
+ *
+ * The message is partitioned by nz_rail_partition(ratios) and each rail by
+ * nz_segment_map; segment j of a rail is the unit of work.
+ *   NZ_FUSED: one launch; every segment is read once from all nodes, summed
+ *     in fp32 registers (int32: wrapping integer add) in a fixed blocked
+ *     pairwise order that depends on n_nodes only, rounded once to `dtype`
+ *     (nearest even) and written once to every distinct output buffer.
+ *   NZ_RING_STEPWISE: 2 (n_nodes - 1) launches, one per ring step, in stream
+ *     order.  Node r sends to node (r+1) mod N; in reduce-scatter step s it
+ *     sends segment (r - s) mod N and the receiver stores
+ *     dtype(fp32(received) + fp32(own)); in allgather step s it sends segment
+ *     (r + 1 - s) mod N and the receiver overwrites its copy.  Partials are
+ *     held in `dtype` between steps, as on a wire.
+ *
+ * Aliasing: out_bufs[i] == node_bufs[i] (in place) is allowed in both modes.
+ * In NZ_FUSED, out_bufs entries may repeat (each distinct buffer is written
+ * once; all equal = one shared result).  Any other overlap between buffers is
+ * NZ_ERR_UNSUPPORTED.  n_elems == 0 returns NZ_OK without launching.
+ */
+nz_status nz_allreduce_sim(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
+                           const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype, nz_mode mode,
+                           void *const *out_bufs, void *stream);
+
+/*
+ * Pack: stage rail segments into contiguous send buffers.  (Sec. 3.2: data
+ * moves from the user's UnboundBuffer into a rail's contiguous Buffer.)
+ *
+ * For every node m, copies segments seg_ids[0..n_segs) of rail `rail` of
+ * node_bufs[m] (device) back to back, in list order and without padding, to
+ * the start of send_bufs[m] (device).  seg_off: host, the table of
+ * nz_segment_map for n_nodes nodes; seg_ids: host, values < n_nodes, may
+ * repeat, n_segs <= NZ_MAX_NODES; elem_bytes 2 or 4.  send_capacity_bytes is
+ * the size of every send buffer (NZ_ERR_CAPACITY if the packed size exceeds
+ * it); packed_bytes (host, may be NULL) receives the packed size per node.
+ * One launch for all nodes.  Source and destination must not overlap.
+ */
+nz_status nz_pack(const void *const *node_bufs, uint32_t n_nodes, const uint64_t *seg_off,
+                  uint32_t n_rails, uint32_t rail, const uint32_t *seg_ids, uint32_t n_segs,
+                  uint32_t elem_bytes, void *const *send_bufs, uint64_t send_capacity_bytes,
+                  uint64_t *packed_bytes, void *stream);
+
+/*
+ * Unpack: the inverse of nz_pack.  (Sec. 3.2: results return from the rail's
+ * Buffer to the UnboundBuffer.)  Scatters the start of send_bufs[m] back into
+ * the listed segments of node_bufs[m]; bytes of node_bufs outside the listed
+ * segments are not touched.  seg_ids must not repeat (NZ_ERR_INVALID_ARG).
+ */
+nz_status nz_unpack(const void *const *send_bufs, uint32_t n_nodes, const uint64_t *seg_off,
+                    uint32_t n_rails, uint32_t rail, const uint32_t *seg_ids, uint32_t n_segs,
+                    uint32_t elem_bytes, void *const *node_bufs, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NEZHA_SIM_H */

@@ -1,0 +1,938 @@
+// HIP kernels (gfx950, wave64) and C-ABI entry points of the allreduce
+// reduction engine: fused N-way reduce + broadcast, ring reduce-scatter and
+// allgather steps, and the segment pack / unpack copy.
+//
+// Nezha (arXiv 2405.17870): the aggregation phase of the allreduce (Sec. 4.2),
+// run per rail on that rail's slice (Sec. 3.4, 4.1), with the ring schedule of
+// Sec. 2.1.1 / Eq. 1, and the staging copies of Sec. 3.2.
+//
+// Everything here is bound by HBM bandwidth (about 0.25 flop per byte), so
+// there is no matrix-core work: the kernels are built around 16-byte
+// coalesced accesses on a 16-byte grid that is common to every buffer (all
+// bases are 256-byte aligned and all nodes use the same element offsets),
+// per-element handling of the few bytes where a segment boundary falls inside
+// a 16-byte vector, and LDS staging only in the copy kernel, the one place
+// where source and destination can be misaligned relative to each other.
+//
+// All per-call tables (node pointers, rail geometry, copy descriptors) travel
+// in the kernel-argument block: no device workspace, no allocation, no
+// host-to-device copy, and a call can be captured in a HIP graph as it is.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <utility>
+#include <vector>
+
+#include "nz_internal.h"
+
+namespace {
+
+typedef uint32_t u32;
+typedef uint64_t u64;
+
+constexpr int kThreads = 256;  // four wave64 per workgroup
+
+// ---------------------------------------------------------------------------
+// Rail / segment geometry, as seen by the kernels
+// ---------------------------------------------------------------------------
+
+// Everything a workgroup needs to find its (rail, segment, tile).  Segment j
+// of rail k covers elements [off[k] + j*q[k] + min(j, rem[k]), +q[k] + (j < rem[k])).
+struct RailGeom {
+    u64 off[NZ_MAX_RAILS + 1];   // rail boundaries, in elements
+    u64 q[NZ_MAX_RAILS];         // short segment length of the rail
+    u32 rem[NZ_MAX_RAILS];       // number of segments that are one element longer
+    u32 tile0[NZ_MAX_RAILS + 1]; // first workgroup of each rail
+    u32 tps[NZ_MAX_RAILS];       // workgroups reserved per segment of the rail
+    u32 n_rails;
+    u32 n_nodes;
+};
+
+// Work of one workgroup: a run of 16-byte vectors of one segment.
+struct SegTile {
+    u64 b0, b1;         // byte range of the whole segment
+    u64 vec_lo, vec_hi; // this workgroup's vectors (global 16-byte vector indices), may be empty
+    u64 tile_base;      // first vector of the aligned tile the run lies in
+};
+
+__device__ __forceinline__ void decode_block(const RailGeom &g, u32 block, u32 &rail, u32 &idx,
+                                             u32 &tile)
+{
+    u32 k = 0;
+    while (k + 1 < g.n_rails && block >= g.tile0[k + 1]) ++k;
+    const u32 local = block - g.tile0[k];
+    rail = k;
+    idx = local / g.tps[k];
+    tile = local - idx * g.tps[k];
+}
+
+// Tiles lie on a grid of TILE_VECS vectors that is global to the buffers, so a
+// workgroup's accesses are aligned to the tile size wherever the segment
+// boundary is; the first and last tile of a segment are simply shorter.
+template <int TILE_VECS>
+__device__ __forceinline__ SegTile segment_tile(const RailGeom &g, u32 rail, u32 seg, u32 tile,
+                                                u32 elem_shift)
+{
+    SegTile t;
+    const u32 rem = g.rem[rail];
+    const u64 beg = g.off[rail] + seg * g.q[rail] + (seg < rem ? seg : rem);
+    const u64 len = g.q[rail] + (seg < rem ? 1u : 0u);
+    t.b0 = beg << elem_shift;
+    t.b1 = (beg + len) << elem_shift;
+    const u64 v0 = t.b0 >> 4;
+    const u64 v1 = (t.b1 + 15) >> 4;
+    t.tile_base = (v0 / TILE_VECS + tile) * TILE_VECS;
+    t.vec_lo = t.tile_base > v0 ? t.tile_base : v0;
+    const u64 end = t.tile_base + TILE_VECS;
+    t.vec_hi = end < v1 ? end : v1;
+    if (len == 0) t.vec_hi = t.vec_lo;
+    return t;
+}
+
+// ---------------------------------------------------------------------------
+// Element types
+// ---------------------------------------------------------------------------
+
+typedef u32 vec16 __attribute__((ext_vector_type(4)));  // one 16-byte access
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ vec16 vec16_of(u32 x, u32 y, u32 z, u32 w)
+{
+    vec16 v = {x, y, z, w};
+    return v;
+}
+__device__ __forceinline__ float as_f32(u32 u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ u32 as_u32(float f) { return __builtin_bit_cast(u32, f); }
+
+// Each type describes how a 16-byte vector (four 32-bit words) and a single
+// element are widened to the accumulator type and narrowed back.  Narrowing
+// rounds to nearest, ties to even, once.
+struct TF32 {
+    typedef float acc_t;
+    typedef u32 elem_t;
+    static constexpr int kShift = 2, kLanes = 4;
+    static __device__ __forceinline__ void widen(const vec16 &v, acc_t (&a)[kLanes])
+    {
+        a[0] = as_f32(v.x); a[1] = as_f32(v.y); a[2] = as_f32(v.z); a[3] = as_f32(v.w);
+    }
+    static __device__ __forceinline__ vec16 narrow(const acc_t (&a)[kLanes])
+    {
+        return vec16_of(as_u32(a[0]), as_u32(a[1]), as_u32(a[2]), as_u32(a[3]));
+    }
+    static __device__ __forceinline__ acc_t widen1(elem_t e) { return as_f32(e); }
+    static __device__ __forceinline__ elem_t narrow1(acc_t a) { return as_u32(a); }
+};
+
+struct TI32 {
+    typedef u32 acc_t;  // wrapping two's-complement add
+    typedef u32 elem_t;
+    static constexpr int kShift = 2, kLanes = 4;
+    static __device__ __forceinline__ void widen(const vec16 &v, acc_t (&a)[kLanes])
+    {
+        a[0] = v.x; a[1] = v.y; a[2] = v.z; a[3] = v.w;
+    }
+    static __device__ __forceinline__ vec16 narrow(const acc_t (&a)[kLanes])
+    {
+        return vec16_of(a[0], a[1], a[2], a[3]);
+    }
+    static __device__ __forceinline__ acc_t widen1(elem_t e) { return e; }
+    static __device__ __forceinline__ elem_t narrow1(acc_t a) { return a; }
+};
+
+struct TBF16 {
+    typedef float acc_t;
+    typedef unsigned short elem_t;
+    static constexpr int kShift = 1, kLanes = 8;
+    // bfloat16 is the upper half of a binary32: widening is a shift or a mask.
+    static __device__ __forceinline__ void widen(const vec16 &v, acc_t (&a)[kLanes])
+    {
+        a[0] = as_f32(v.x << 16); a[1] = as_f32(v.x & 0xffff0000u);
+        a[2] = as_f32(v.y << 16); a[3] = as_f32(v.y & 0xffff0000u);
+        a[4] = as_f32(v.z << 16); a[5] = as_f32(v.z & 0xffff0000u);
+        a[6] = as_f32(v.w << 16); a[7] = as_f32(v.w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ u32 pair(float lo, float hi)
+    {
+        f32x2 f = {lo, hi};
+        return __builtin_bit_cast(u32, __builtin_convertvector(f, bf16x2));  // v_cvt_pk_bf16_f32
+    }
+    static __device__ __forceinline__ vec16 narrow(const acc_t (&a)[kLanes])
+    {
+        return vec16_of(pair(a[0], a[1]), pair(a[2], a[3]), pair(a[4], a[5]), pair(a[6], a[7]));
+    }
+    static __device__ __forceinline__ acc_t widen1(elem_t e) { return as_f32((u32)e << 16); }
+    static __device__ __forceinline__ elem_t narrow1(acc_t a)
+    {
+        return __builtin_bit_cast(unsigned short, (__bf16)a);
+    }
+};
+
+struct TF16 {
+    typedef float acc_t;
+    typedef unsigned short elem_t;
+    static constexpr int kShift = 1, kLanes = 8;
+    static __device__ __forceinline__ void widen2(u32 w, float &lo, float &hi)
+    {
+        f16x2 h = __builtin_bit_cast(f16x2, w);
+        lo = (float)h.x;
+        hi = (float)h.y;
+    }
+    static __device__ __forceinline__ void widen(const vec16 &v, acc_t (&a)[kLanes])
+    {
+        widen2(v.x, a[0], a[1]); widen2(v.y, a[2], a[3]);
+        widen2(v.z, a[4], a[5]); widen2(v.w, a[6], a[7]);
+    }
+    static __device__ __forceinline__ u32 pair(float lo, float hi)
+    {
+        f16x2 h = {(_Float16)lo, (_Float16)hi};
+        return __builtin_bit_cast(u32, h);
+    }
+    static __device__ __forceinline__ vec16 narrow(const acc_t (&a)[kLanes])
+    {
+        return vec16_of(pair(a[0], a[1]), pair(a[2], a[3]), pair(a[4], a[5]), pair(a[6], a[7]));
+    }
+    static __device__ __forceinline__ acc_t widen1(elem_t e)
+    {
+        return (float)__builtin_bit_cast(_Float16, e);
+    }
+    static __device__ __forceinline__ elem_t narrow1(acc_t a)
+    {
+        return __builtin_bit_cast(unsigned short, (_Float16)a);
+    }
+};
+
+// A "packet" is what one thread carries per node: either a whole 16-byte
+// vector (the body of a segment) or a single element (the few bytes where a
+// segment boundary falls inside a vector).  Both go through the same
+// summation code, so an element's sum does not depend on which path took it.
+template <class T>
+struct VecPacket {
+    typedef vec16 raw_t;
+    static constexpr int kLanes = T::kLanes;
+    static __device__ __forceinline__ raw_t load(const void *base, u64 byte_off)
+    {
+        return __builtin_nontemporal_load(
+            reinterpret_cast<const vec16 *>(static_cast<const char *>(base) + byte_off));
+    }
+    static __device__ __forceinline__ void store(void *base, u64 byte_off, const raw_t &v)
+    {
+        __builtin_nontemporal_store(v,
+                                    reinterpret_cast<vec16 *>(static_cast<char *>(base) + byte_off));
+    }
+    static __device__ __forceinline__ void widen(const raw_t &r, typename T::acc_t (&a)[kLanes])
+    {
+        T::widen(r, a);
+    }
+    static __device__ __forceinline__ raw_t narrow(const typename T::acc_t (&a)[kLanes])
+    {
+        return T::narrow(a);
+    }
+};
+
+template <class T>
+struct ElemPacket {
+    typedef typename T::elem_t raw_t;
+    static constexpr int kLanes = 1;
+    static __device__ __forceinline__ raw_t load(const void *base, u64 byte_off)
+    {
+        return *reinterpret_cast<const raw_t *>(static_cast<const char *>(base) + byte_off);
+    }
+    static __device__ __forceinline__ void store(void *base, u64 byte_off, const raw_t &v)
+    {
+        *reinterpret_cast<raw_t *>(static_cast<char *>(base) + byte_off) = v;
+    }
+    static __device__ __forceinline__ void widen(const raw_t &r, typename T::acc_t (&a)[1])
+    {
+        a[0] = T::widen1(r);
+    }
+    static __device__ __forceinline__ raw_t narrow(const typename T::acc_t (&a)[1])
+    {
+        return T::narrow1(a[0]);
+    }
+};
+
+// ---------------------------------------------------------------------------
+// Fused N-way reduce + broadcast
+// ---------------------------------------------------------------------------
+
+struct FusedArgs {
+    RailGeom g;
+    u32 n_out;  // distinct output buffers
+    u32 elem_shift;
+    const void *in[NZ_MAX_NODES];
+    void *out[NZ_MAX_NODES];
+};
+
+// Sum of one packet position over all nodes, in a fixed order that depends on
+// the node count alone:
+//   - nodes are taken in blocks of eight consecutive indices; the values of a
+//     block are added as a balanced binary tree (an operand that does not
+//     exist is skipped, never replaced by zero);
+//   - block sums go round-robin into four running sums (block b into b mod 4);
+//   - the running sums are added as (s0 + s1) + (s2 + s3).
+// With N <= 128 no value passes through more than 3 + 3 + 2 roundings, so the
+// fp32 error stays below 8 * 2^-24 * sum|x|, and the eight loads of a block
+// are independent and in flight together.
+template <class T, class P>
+__device__ __forceinline__ void reduce_nodes(const FusedArgs &a, u64 byte_off,
+                                             typename T::acc_t (&res)[P::kLanes])
+{
+    typedef typename T::acc_t acc_t;
+    constexpr int L = P::kLanes;
+    const u32 N = a.g.n_nodes;
+    acc_t run[4][L];
+
+    for (u32 base = 0; base < N; base += 32) {
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const u32 m0 = base + c * 8;
+            if (m0 >= N) break;
+            const u32 nb = (N - m0 < 8u) ? (N - m0) : 8u;
+            acc_t s[L];
+            if (nb == 8) {
+                typename P::raw_t r[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) r[i] = P::load(a.in[m0 + i], byte_off);
+                acc_t v[8][L];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) P::widen(r[i], v[i]);
+#pragma unroll
+                for (int l = 0; l < L; ++l)
+                    s[l] = ((v[0][l] + v[1][l]) + (v[2][l] + v[3][l])) +
+                           ((v[4][l] + v[5][l]) + (v[6][l] + v[7][l]));
+            } else {
+                // Last, partial block: same tree with the missing leaves left out.
+                typename P::raw_t r[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if ((u32)i < nb) r[i] = P::load(a.in[m0 + i], byte_off);
+                acc_t v[8][L];
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if ((u32)i < nb) P::widen(r[i], v[i]);
+#pragma unroll
+                for (int l = 0; l < L; ++l) {
+                    acc_t p[4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if ((u32)(2 * i) < nb)
+                            p[i] = ((u32)(2 * i + 1) < nb) ? v[2 * i][l] + v[2 * i + 1][l] : v[2 * i][l];
+                    acc_t lo = (nb > 2) ? p[0] + p[1] : p[0];
+                    if (nb > 4) {
+                        acc_t hi = (nb > 6) ? p[2] + p[3] : p[2];
+                        lo = lo + hi;
+                    }
+                    s[l] = lo;
+                }
+            }
+            if (base == 0) {
+#pragma unroll
+                for (int l = 0; l < L; ++l) run[c][l] = s[l];
+            } else {
+#pragma unroll
+                for (int l = 0; l < L; ++l) run[c][l] = run[c][l] + s[l];
+            }
+        }
+    }
+#pragma unroll
+    for (int l = 0; l < L; ++l) {
+        acc_t t = run[0][l];
+        if (N > 8) t = t + run[1][l];
+        if (N > 16) {
+            acc_t u = run[2][l];
+            if (N > 24) u = u + run[3][l];
+            t = t + u;
+        }
+        res[l] = t;
+    }
+}
+
+template <class T, class P>
+__device__ __forceinline__ void reduce_bcast_at(const FusedArgs &a, u64 byte_off)
+{
+    typename T::acc_t res[P::kLanes];
+    reduce_nodes<T, P>(a, byte_off, res);
+    const typename P::raw_t packed = P::narrow(res);
+    for (u32 o = 0; o < a.n_out; ++o) P::store(a.out[o], byte_off, packed);
+}
+
+// One workgroup = one aligned tile of ITERS * 256 vectors of one segment.
+template <class T, int ITERS>
+__global__ __launch_bounds__(kThreads) void nz_fused_reduce_bcast(const FusedArgs a)
+{
+    constexpr int TILE = ITERS * kThreads;
+    u32 rail, seg, tile;
+    decode_block(a.g, blockIdx.x, rail, seg, tile);
+    const SegTile t = segment_tile<TILE>(a.g, rail, seg, tile, T::kShift);
+    if (t.vec_lo >= t.vec_hi) return;
+
+    // Vectors that lie wholly inside the segment.
+    const u64 full_lo = (t.b0 + 15) >> 4, full_hi = t.b1 >> 4;
+    const u64 lo = t.vec_lo > full_lo ? t.vec_lo : full_lo;
+    const u64 hi = t.vec_hi < full_hi ? t.vec_hi : full_hi;
+#pragma unroll 1
+    for (int it = 0; it < ITERS; ++it) {
+        const u64 vec = t.tile_base + (u64)it * kThreads + threadIdx.x;
+        if (vec >= lo && vec < hi) reduce_bcast_at<T, VecPacket<T>>(a, vec << 4);
+    }
+
+    // Elements of the segment that share a vector with a neighbouring segment
+    // (or with the end of the buffer): one thread per element.
+    const u64 head_end = (full_lo << 4) < t.b1 ? (full_lo << 4) : t.b1;
+    u64 tail_beg = full_hi << 4;
+    if (tail_beg < head_end) tail_beg = head_end;
+    const u64 eoff = (u64)threadIdx.x << T::kShift;
+    if (t.vec_lo == (t.b0 >> 4) && t.b0 + eoff < head_end)
+        reduce_bcast_at<T, ElemPacket<T>>(a, t.b0 + eoff);
+    if (t.vec_hi == ((t.b1 + 15) >> 4) && tail_beg + eoff < t.b1)
+        reduce_bcast_at<T, ElemPacket<T>>(a, tail_beg + eoff);
+}
+
+// ---------------------------------------------------------------------------
+// Ring steps
+// ---------------------------------------------------------------------------
+
+struct RingArgs {
+    RailGeom g;
+    u32 step;        // s = 0 .. N-2
+    u32 elem_shift;
+    const void *in[NZ_MAX_NODES];
+    void *out[NZ_MAX_NODES];
+};
+
+// Reduce-scatter step s: node r sends segment (r - s) mod N to node d = r + 1;
+// d stores dtype(fp32(received) + fp32(own)).  What r sends is its own input
+// in step 0 and the partial it stored in step s - 1 afterwards.
+// Allgather step s: node r sends the complete segment (r + 1 - s) mod N; d
+// overwrites its copy.
+template <class T, class P, bool GATHER>
+__device__ __forceinline__ void ring_at(const void *sent, const void *own, void *dst, u64 byte_off)
+{
+    if (GATHER) {
+        P::store(dst, byte_off, P::load(sent, byte_off));
+    } else {
+        typename T::acc_t x[P::kLanes], y[P::kLanes];
+        const typename P::raw_t rs = P::load(sent, byte_off);
+        const typename P::raw_t ro = P::load(own, byte_off);
+        P::widen(rs, x);
+        P::widen(ro, y);
+#pragma unroll
+        for (int l = 0; l < P::kLanes; ++l) x[l] = x[l] + y[l];
+        P::store(dst, byte_off, P::narrow(x));
+    }
+}
+
+template <class T, int ITERS, bool GATHER>
+__global__ __launch_bounds__(kThreads) void nz_ring_step(const RingArgs a)
+{
+    constexpr int TILE = ITERS * kThreads;
+    u32 rail, r, tile;
+    decode_block(a.g, blockIdx.x, rail, r, tile);
+    const u32 N = a.g.n_nodes;
+    const u32 d = (r + 1 == N) ? 0 : r + 1;
+    const u32 seg = GATHER ? (r + 1 + N - a.step) % N : (r + N - a.step) % N;
+    const SegTile t = segment_tile<TILE>(a.g, rail, seg, tile, T::kShift);
+    if (t.vec_lo >= t.vec_hi) return;
+
+    const void *sent = (GATHER || a.step > 0) ? a.out[r] : a.in[r];
+    const void *own = a.in[d];
+    void *dst = a.out[d];
+
+    const u64 full_lo = (t.b0 + 15) >> 4, full_hi = t.b1 >> 4;
+    const u64 lo = t.vec_lo > full_lo ? t.vec_lo : full_lo;
+    const u64 hi = t.vec_hi < full_hi ? t.vec_hi : full_hi;
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const u64 vec = t.tile_base + (u64)it * kThreads + threadIdx.x;
+        if (vec >= lo && vec < hi) ring_at<T, VecPacket<T>, GATHER>(sent, own, dst, vec << 4);
+    }
+    const u64 head_end = (full_lo << 4) < t.b1 ? (full_lo << 4) : t.b1;
+    u64 tail_beg = full_hi << 4;
+    if (tail_beg < head_end) tail_beg = head_end;
+    const u64 eoff = (u64)threadIdx.x << T::kShift;
+    if (t.vec_lo == (t.b0 >> 4) && t.b0 + eoff < head_end)
+        ring_at<T, ElemPacket<T>, GATHER>(sent, own, dst, t.b0 + eoff);
+    if (t.vec_hi == ((t.b1 + 15) >> 4) && tail_beg + eoff < t.b1)
+        ring_at<T, ElemPacket<T>, GATHER>(sent, own, dst, tail_beg + eoff);
+}
+
+// ---------------------------------------------------------------------------
+// Segment copy (pack / unpack)
+// ---------------------------------------------------------------------------
+
+constexpr int kCopyMaxRuns = 40;  // runs per launch; longer lists take several launches
+constexpr int kCopyIters = 4;     // 256-vector sub-tiles per workgroup
+
+// One run: len bytes from src_off in every source buffer to dst_off in the
+// matching destination buffer.  All three are multiples of the element size.
+struct CopyArgs {
+    u64 src_off[kCopyMaxRuns];
+    u64 dst_off[kCopyMaxRuns];
+    u64 len[kCopyMaxRuns];
+    u32 tile0[kCopyMaxRuns + 1];  // first workgroup (per node) of each run
+    u32 n_runs;
+    u32 elem_bytes;
+    const void *src[NZ_MAX_NODES];
+    void *dst[NZ_MAX_NODES];
+};
+
+// Tiles lie on the destination's 16-byte grid, so every store is an aligned
+// 16-byte store.  When the source of a run sits at another offset within its
+// 16 bytes (shift != 0), the workgroup stages the aligned source vectors that
+// cover its tile in LDS and each thread assembles its destination vector from
+// five consecutive 32-bit LDS words; with shift == 0 it is a plain vector copy.
+// Bytes of the run outside whole destination vectors, and destination vectors
+// whose source words are not all inside the run, are copied element by
+// element, so no access ever leaves [off, off + len) of either buffer.
+__global__ __launch_bounds__(kThreads) void nz_segment_copy(const CopyArgs a)
+{
+    __shared__ vec16 stage[kThreads + 1];
+
+    const u32 node = blockIdx.y;
+    u32 run = 0;
+    while (run + 1 < a.n_runs && blockIdx.x >= a.tile0[run + 1]) ++run;
+    const u32 tile = blockIdx.x - a.tile0[run];
+
+    const char *src = static_cast<const char *>(a.src[node]);
+    char *dst = static_cast<char *>(a.dst[node]);
+    const u64 S = a.src_off[run], D = a.dst_off[run], L = a.len[run];
+    const u64 d_end = D + L;
+    const u64 full_lo = (D + 15) >> 4, full_hi = d_end >> 4;  // whole destination vectors
+    const u32 shift = (u32)((S - D) & 15);
+    // Aligned source vectors that lie wholly inside the run.
+    const u64 src_full_lo = (S + 15) >> 4, src_full_hi = (S + L) >> 4;
+
+    constexpr int TILE = kCopyIters * kThreads;
+    const u64 tile_base = ((D >> 4) / TILE + tile) * (u64)TILE;
+
+#pragma unroll 1
+    for (int it = 0; it < kCopyIters; ++it) {
+        const u64 sub = tile_base + (u64)it * kThreads;  // first destination vector of the sub-tile
+        if (sub >= ((d_end + 15) >> 4)) break;           // uniform: past the run
+        const u64 w = sub + threadIdx.x;
+        const bool whole = (w >= full_lo && w < full_hi);
+        if (shift == 0) {
+            if (whole) {
+                const u64 sb = (w << 4) - D + S;
+                const vec16 v = __builtin_nontemporal_load(reinterpret_cast<const vec16 *>(src + sb));
+                __builtin_nontemporal_store(v, reinterpret_cast<vec16 *>(dst + (w << 4)));
+            }
+            continue;
+        }
+        // Source position of destination byte 16 * sub, rounded down to a vector.
+        // For the first sub-tile it can lie in front of the source buffer, hence
+        // signed arithmetic; only vectors wholly inside the run are touched.
+        const long long s_first = (long long)(sub << 4) - (long long)D + (long long)S;
+        const long long sv0 = (s_first - (long long)shift) >> 4;  // exact: s_first = shift mod 16
+        __syncthreads();                                          // previous sub-tile's readers are done
+        for (u32 i = threadIdx.x; i < kThreads + 1; i += kThreads) {
+            const long long sv = sv0 + i;
+            if (sv >= (long long)src_full_lo && sv < (long long)src_full_hi)
+                stage[i] = __builtin_nontemporal_load(reinterpret_cast<const vec16 *>(src + (sv << 4)));
+        }
+        __syncthreads();
+        const long long sv = sv0 + threadIdx.x;
+        const bool staged = whole && sv >= (long long)src_full_lo && sv + 1 < (long long)src_full_hi;
+        if (staged) {
+            const u32 *words = reinterpret_cast<const u32 *>(stage) + threadIdx.x * 4 + (shift >> 2);
+            const u32 w0 = words[0], w1 = words[1], w2 = words[2], w3 = words[3], w4 = words[4];
+            const u32 sh = shift & 3;  // 0 or 2 bytes
+            vec16 v;
+            v.x = __builtin_amdgcn_alignbyte(w1, w0, sh);
+            v.y = __builtin_amdgcn_alignbyte(w2, w1, sh);
+            v.z = __builtin_amdgcn_alignbyte(w3, w2, sh);
+            v.w = __builtin_amdgcn_alignbyte(w4, w3, sh);
+            __builtin_nontemporal_store(v, reinterpret_cast<vec16 *>(dst + (w << 4)));
+        } else if (whole) {
+            // A whole destination vector at the very edge of the run's source.
+            const u64 sb = (w << 4) - D + S;
+            if (a.elem_bytes == 4) {
+                for (int i = 0; i < 4; ++i)
+                    reinterpret_cast<u32 *>(dst + (w << 4))[i] = reinterpret_cast<const u32 *>(src + sb)[i];
+            } else {
+                for (int i = 0; i < 8; ++i)
+                    reinterpret_cast<unsigned short *>(dst + (w << 4))[i] =
+                        reinterpret_cast<const unsigned short *>(src + sb)[i];
+            }
+        }
+    }
+
+    // Bytes of the run that are not in a whole destination vector.
+    const u64 head_end = (full_lo << 4) < d_end ? (full_lo << 4) : d_end;
+    u64 tail_beg = full_hi << 4;
+    if (tail_beg < head_end) tail_beg = head_end;
+    const u64 eoff = (u64)threadIdx.x * a.elem_bytes;
+    const u64 first_tile_base = ((D >> 4) / TILE) * (u64)TILE;
+    const u64 last_tile_base = (((d_end + 15) >> 4) - 1) / TILE * (u64)TILE;
+    if (tile_base == first_tile_base && D + eoff < head_end) {
+        if (a.elem_bytes == 4)
+            *reinterpret_cast<u32 *>(dst + D + eoff) = *reinterpret_cast<const u32 *>(src + S + eoff);
+        else
+            *reinterpret_cast<unsigned short *>(dst + D + eoff) =
+                *reinterpret_cast<const unsigned short *>(src + S + eoff);
+    }
+    if (tile_base == last_tile_base && tail_beg + eoff < d_end) {
+        const u64 sb = tail_beg + eoff - D + S;
+        if (a.elem_bytes == 4)
+            *reinterpret_cast<u32 *>(dst + tail_beg + eoff) = *reinterpret_cast<const u32 *>(src + sb);
+        else
+            *reinterpret_cast<unsigned short *>(dst + tail_beg + eoff) =
+                *reinterpret_cast<const unsigned short *>(src + sb);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Host side
+// ---------------------------------------------------------------------------
+
+thread_local char g_hip_error[256] = "";
+
+nz_status hip_failed(hipError_t e, const char *what)
+{
+    std::snprintf(g_hip_error, sizeof g_hip_error, "%s: %s", what, hipGetErrorString(e));
+    return NZ_ERR_HIP;
+}
+
+bool aligned256(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
+
+// Fill the geometry for tiles of tile_vecs 16-byte vectors.  Returns the
+// number of workgroups, or 0 if it does not fit the grid.
+u64 build_geometry(RailGeom &g, const u64 *rail_off, u32 n_rails, u32 n_nodes, u32 elem_shift,
+                   u32 tile_vecs)
+{
+    std::memset(&g, 0, sizeof g);
+    g.n_rails = n_rails;
+    g.n_nodes = n_nodes;
+    u64 total = 0;
+    for (u32 k = 0; k < n_rails; ++k) {
+        const u64 len = rail_off[k + 1] - rail_off[k];
+        g.off[k] = rail_off[k];
+        g.q[k] = len / n_nodes;
+        g.rem[k] = (u32)(len % n_nodes);
+        // Exact maximum, over the rail's segments, of the tiles a segment touches.
+        u64 most = 0;
+        for (u32 j = 0; j < n_nodes && len > 0; ++j) {
+            const u64 beg = g.off[k] + j * g.q[k] + std::min<u64>(j, g.rem[k]);
+            const u64 sl = g.q[k] + (j < g.rem[k] ? 1 : 0);
+            if (sl == 0) continue;
+            const u64 v0 = (beg << elem_shift) >> 4;
+            const u64 v1 = (((beg + sl) << elem_shift) + 15) >> 4;
+            most = std::max<u64>(most, (v1 - 1) / tile_vecs - v0 / tile_vecs + 1);
+        }
+        if (most > 0xffffffffull) return 0;
+        g.tps[k] = (u32)most;
+        g.tile0[k] = (u32)total;
+        total += most * n_nodes;
+        if (total > 0x7fffffffull) return 0;
+    }
+    g.off[n_rails] = rail_off[n_rails];
+    g.tile0[n_rails] = (u32)total;
+    return total;
+}
+
+struct PtrRef {
+    uintptr_t p;
+    bool written;
+};
+
+// Buffers of `bytes` bytes each: a written buffer may not partially overlap
+// any other buffer.
+bool partial_overlap(std::vector<PtrRef> &v, u64 bytes)
+{
+    std::sort(v.begin(), v.end(), [](const PtrRef &x, const PtrRef &y) { return x.p < y.p; });
+    // merge equal pointers
+    size_t w = 0;
+    for (size_t i = 0; i < v.size(); ++i) {
+        if (w > 0 && v[w - 1].p == v[i].p)
+            v[w - 1].written = v[w - 1].written || v[i].written;
+        else
+            v[w++] = v[i];
+    }
+    v.resize(w);
+    for (size_t i = 0; i + 1 < v.size(); ++i)
+        if (v[i + 1].p - v[i].p < bytes && (v[i].written || v[i + 1].written)) return true;
+    return false;
+}
+
+struct Range {
+    uintptr_t lo, hi;
+    bool written;
+};
+
+// True if a written range overlaps any other range (read ranges may overlap
+// each other freely).
+bool written_range_overlaps(std::vector<Range> &v)
+{
+    std::sort(v.begin(), v.end(), [](const Range &x, const Range &y) { return x.lo < y.lo; });
+    uintptr_t end_any = 0, end_written = 0;
+    for (const Range &r : v) {
+        if (r.lo == r.hi) continue;
+        if (r.written ? r.lo < end_any : r.lo < end_written) return true;
+        end_any = std::max(end_any, r.hi);
+        if (r.written) end_written = std::max(end_written, r.hi);
+    }
+    return false;
+}
+
+template <class T>
+nz_status launch_fused(const FusedArgs &a, u32 blocks, hipStream_t st, int iters)
+{
+    switch (iters) {
+    case 1: hipLaunchKernelGGL((nz_fused_reduce_bcast<T, 1>), dim3(blocks), dim3(kThreads), 0, st, a); break;
+    case 2: hipLaunchKernelGGL((nz_fused_reduce_bcast<T, 2>), dim3(blocks), dim3(kThreads), 0, st, a); break;
+    default: hipLaunchKernelGGL((nz_fused_reduce_bcast<T, 4>), dim3(blocks), dim3(kThreads), 0, st, a); break;
+    }
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? NZ_OK : hip_failed(e, "fused reduce launch");
+}
+
+constexpr int kRingIters = 4;
+
+template <class T>
+nz_status launch_ring(RingArgs &a, u32 blocks, hipStream_t st)
+{
+    const u32 N = a.g.n_nodes;
+    for (u32 s = 0; s + 1 < N; ++s) {
+        a.step = s;
+        hipLaunchKernelGGL((nz_ring_step<T, kRingIters, false>), dim3(blocks), dim3(kThreads), 0, st, a);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_failed(e, "ring reduce-scatter launch");
+    }
+    for (u32 s = 0; s + 1 < N; ++s) {
+        a.step = s;
+        hipLaunchKernelGGL((nz_ring_step<T, kRingIters, true>), dim3(blocks), dim3(kThreads), 0, st, a);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_failed(e, "ring allgather launch");
+    }
+    return NZ_OK;
+}
+
+int g_fused_iters = 1;  // 256-vector sub-tiles per workgroup of the fused kernel
+
+nz_status segment_copy(const void *const *src, void *const *dst, u32 n_nodes, const u64 *seg_off,
+                       u32 n_rails, u32 rail, const u32 *seg_ids, u32 n_segs, u32 elem_bytes,
+                       bool packing, u64 capacity, u64 *packed_bytes, hipStream_t st)
+{
+    if (src == nullptr || dst == nullptr || seg_off == nullptr) return NZ_ERR_INVALID_ARG;
+    if (n_nodes == 0 || n_rails == 0 || rail >= n_rails) return NZ_ERR_INVALID_ARG;
+    if (n_segs > 0 && seg_ids == nullptr) return NZ_ERR_INVALID_ARG;
+    if (elem_bytes != 2 && elem_bytes != 4) return NZ_ERR_INVALID_ARG;
+    if (n_nodes > NZ_MAX_NODES || n_rails > NZ_MAX_RAILS || n_segs > NZ_MAX_NODES)
+        return NZ_ERR_UNSUPPORTED;
+    const u64 *row = seg_off + (size_t)rail * (n_nodes + 1);
+    for (u32 j = 0; j < n_nodes; ++j)
+        if (row[j + 1] < row[j] || row[j + 1] > (UINT64_MAX >> 3)) return NZ_ERR_INVALID_ARG;
+    std::vector<bool> seen(n_nodes, false);
+    u64 total = 0;
+    for (u32 i = 0; i < n_segs; ++i) {
+        if (seg_ids[i] >= n_nodes) return NZ_ERR_INVALID_ARG;
+        if (!packing) {
+            if (seen[seg_ids[i]]) return NZ_ERR_INVALID_ARG;
+            seen[seg_ids[i]] = true;
+        }
+        total += (row[seg_ids[i] + 1] - row[seg_ids[i]]) * elem_bytes;
+    }
+    if (packing && total > capacity) return NZ_ERR_CAPACITY;
+    const u64 node_span_lo = row[0] * elem_bytes, node_span_hi = row[n_nodes] * elem_bytes;
+    for (u32 m = 0; m < n_nodes; ++m) {
+        if (src[m] == nullptr || dst[m] == nullptr) return NZ_ERR_INVALID_ARG;
+        if (!aligned256(src[m]) || !aligned256(dst[m])) return NZ_ERR_ALIGNMENT;
+    }
+    // A written range may not overlap any other range.  The packed side of
+    // buffer m is [base, base + total), the node side is the rail's span.
+    {
+        std::vector<Range> ranges;
+        ranges.reserve(2 * n_nodes);
+        for (u32 m = 0; m < n_nodes && total > 0; ++m) {
+            const uintptr_t s0 = reinterpret_cast<uintptr_t>(src[m]), d0 = reinterpret_cast<uintptr_t>(dst[m]);
+            if (packing) {
+                ranges.push_back({s0 + node_span_lo, s0 + node_span_hi, false});
+                ranges.push_back({d0, d0 + total, true});
+            } else {
+                ranges.push_back({s0, s0 + total, false});
+                ranges.push_back({d0 + node_span_lo, d0 + node_span_hi, true});
+            }
+        }
+        if (written_range_overlaps(ranges)) return NZ_ERR_UNSUPPORTED;
+    }
+    if (packed_bytes) *packed_bytes = total;
+    if (total == 0) return NZ_OK;
+
+    // Runs: consecutive list entries that are also consecutive in the node
+    // buffer merge into one (a whole rail in order is a single run).
+    struct Run { u64 node_off, pack_off, len; };
+    std::vector<Run> runs;
+    u64 pos = 0;
+    for (u32 i = 0; i < n_segs; ++i) {
+        const u64 off = row[seg_ids[i]] * elem_bytes;
+        const u64 len = (row[seg_ids[i] + 1] - row[seg_ids[i]]) * elem_bytes;
+        if (len == 0) continue;
+        if (!runs.empty() && runs.back().node_off + runs.back().len == off)
+            runs.back().len += len;
+        else
+            runs.push_back({off, pos, len});
+        pos += len;
+    }
+
+    constexpr u64 TILE = (u64)kCopyIters * kThreads;
+    size_t next = 0;
+    while (next < runs.size()) {
+        CopyArgs a;
+        std::memset(&a, 0, sizeof a);
+        a.elem_bytes = elem_bytes;
+        u64 blocks = 0;
+        u32 r = 0;
+        for (; r < (u32)kCopyMaxRuns && next < runs.size(); ++r, ++next) {
+            const Run &run = runs[next];
+            a.src_off[r] = packing ? run.node_off : run.pack_off;
+            a.dst_off[r] = packing ? run.pack_off : run.node_off;
+            a.len[r] = run.len;
+            a.tile0[r] = (u32)blocks;
+            const u64 v0 = a.dst_off[r] >> 4, v1 = (a.dst_off[r] + run.len + 15) >> 4;
+            blocks += (v1 - 1) / TILE - v0 / TILE + 1;
+            if (blocks > 0x7fffffffull) return NZ_ERR_UNSUPPORTED;
+        }
+        a.tile0[r] = (u32)blocks;
+        a.n_runs = r;
+        for (u32 m = 0; m < n_nodes; ++m) {
+            a.src[m] = src[m];
+            a.dst[m] = dst[m];
+        }
+        hipLaunchKernelGGL(nz_segment_copy, dim3((u32)blocks, n_nodes), dim3(kThreads), 0, st, a);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_failed(e, "segment copy launch");
+    }
+    return NZ_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *nz_last_hip_error(void) { return g_hip_error; }
+
+// Tuning hook: 256-vector sub-tiles per workgroup of the fused kernel (1, 2 or 4).
+void nz_set_fused_tile_iters(int iters) { g_fused_iters = (iters == 2 || iters == 4) ? iters : 1; }
+
+nz_status nz_allreduce_sim(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
+                           const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype, nz_mode mode,
+                           void *const *out_bufs, void *stream)
+{
+    if (node_bufs == nullptr || out_bufs == nullptr || ratios == nullptr) return NZ_ERR_INVALID_ARG;
+    if (n_nodes == 0 || n_rails == 0) return NZ_ERR_INVALID_ARG;
+    const u32 eb = nz_dtype_bytes(dtype);
+    if (eb == 0) return NZ_ERR_INVALID_ARG;
+    if (mode != NZ_RING_STEPWISE && mode != NZ_FUSED) return NZ_ERR_INVALID_ARG;
+    if (n_nodes > NZ_MAX_NODES || n_rails > NZ_MAX_RAILS) return NZ_ERR_UNSUPPORTED;
+
+    u64 rail_off[NZ_MAX_RAILS + 1];
+    const nz_status ps = nz::rail_partition(n_elems, eb, NZ_RAIL_ALIGN_BYTES, ratios, n_rails, rail_off);
+    if (ps != NZ_OK) return ps;
+
+    for (u32 i = 0; i < n_nodes; ++i) {
+        if (node_bufs[i] == nullptr || out_bufs[i] == nullptr) return NZ_ERR_INVALID_ARG;
+        if (!aligned256(node_bufs[i]) || !aligned256(out_bufs[i])) return NZ_ERR_ALIGNMENT;
+    }
+    const u64 bytes = n_elems * eb;
+    {
+        std::vector<PtrRef> refs;
+        refs.reserve(2 * n_nodes);
+        for (u32 i = 0; i < n_nodes; ++i) {
+            refs.push_back({reinterpret_cast<uintptr_t>(node_bufs[i]), false});
+            refs.push_back({reinterpret_cast<uintptr_t>(out_bufs[i]), true});
+        }
+        if (partial_overlap(refs, bytes)) return NZ_ERR_UNSUPPORTED;
+    }
+    if (mode == NZ_RING_STEPWISE) {
+        // Outputs pairwise distinct; an output may alias only its own node's input.
+        std::vector<std::pair<uintptr_t, u32>> ins, outs;
+        for (u32 i = 0; i < n_nodes; ++i) {
+            ins.push_back({reinterpret_cast<uintptr_t>(node_bufs[i]), i});
+            outs.push_back({reinterpret_cast<uintptr_t>(out_bufs[i]), i});
+        }
+        std::sort(ins.begin(), ins.end());
+        std::sort(outs.begin(), outs.end());
+        for (u32 i = 0; i + 1 < n_nodes; ++i)
+            if (outs[i].first == outs[i + 1].first) return NZ_ERR_UNSUPPORTED;
+        for (u32 i = 0; i < n_nodes; ++i) {
+            auto it = std::lower_bound(ins.begin(), ins.end(), std::make_pair(outs[i].first, 0u));
+            for (; it != ins.end() && it->first == outs[i].first; ++it)
+                if (it->second != outs[i].second) return NZ_ERR_UNSUPPORTED;
+        }
+    }
+    if (n_elems == 0) return NZ_OK;
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const u32 shift = (eb == 4) ? 2 : 1;
+
+    if (mode == NZ_FUSED) {
+        FusedArgs a;
+        const int iters = g_fused_iters;
+        const u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, (u32)iters * kThreads);
+        if (blocks == 0) return NZ_ERR_UNSUPPORTED;
+        a.elem_shift = shift;
+        a.n_out = 0;
+        for (u32 i = 0; i < n_nodes; ++i) {
+            a.in[i] = node_bufs[i];
+            bool dup = false;
+            for (u32 o = 0; o < a.n_out; ++o) dup = dup || (a.out[o] == out_bufs[i]);
+            if (!dup) a.out[a.n_out++] = out_bufs[i];
+        }
+        switch (dtype) {
+        case NZ_F32: return launch_fused<TF32>(a, (u32)blocks, st, iters);
+        case NZ_I32: return launch_fused<TI32>(a, (u32)blocks, st, iters);
+        case NZ_BF16: return launch_fused<TBF16>(a, (u32)blocks, st, iters);
+        case NZ_F16: return launch_fused<TF16>(a, (u32)blocks, st, iters);
+        }
+        return NZ_ERR_INVALID_ARG;
+    }
+
+    RingArgs a;
+    const u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, (u32)kRingIters * kThreads);
+    if (blocks == 0) return NZ_ERR_UNSUPPORTED;
+    a.elem_shift = shift;
+    a.step = 0;
+    for (u32 i = 0; i < n_nodes; ++i) {
+        a.in[i] = node_bufs[i];
+        a.out[i] = out_bufs[i];
+    }
+    if (n_nodes == 1) {
+        // A ring of one node has no steps: the result is the node's own data.
+        if (out_bufs[0] != node_bufs[0]) {
+            const hipError_t e = hipMemcpyAsync(out_bufs[0], node_bufs[0], bytes, hipMemcpyDeviceToDevice, st);
+            if (e != hipSuccess) return hip_failed(e, "single-node copy");
+        }
+        return NZ_OK;
+    }
+    switch (dtype) {
+    case NZ_F32: return launch_ring<TF32>(a, (u32)blocks, st);
+    case NZ_I32: return launch_ring<TI32>(a, (u32)blocks, st);
+    case NZ_BF16: return launch_ring<TBF16>(a, (u32)blocks, st);
+    case NZ_F16: return launch_ring<TF16>(a, (u32)blocks, st);
+    }
+    return NZ_ERR_INVALID_ARG;
+}
+
+nz_status nz_pack(const void *const *node_bufs, uint32_t n_nodes, const uint64_t *seg_off,
+                  uint32_t n_rails, uint32_t rail, const uint32_t *seg_ids, uint32_t n_segs,
+                  uint32_t elem_bytes, void *const *send_bufs, uint64_t send_capacity_bytes,
+                  uint64_t *packed_bytes, void *stream)
+{
+    return segment_copy(node_bufs, send_bufs, n_nodes, seg_off, n_rails, rail, seg_ids, n_segs,
+                        elem_bytes, true, send_capacity_bytes, packed_bytes,
+                        static_cast<hipStream_t>(stream));
+}
+
+nz_status nz_unpack(const void *const *send_bufs, uint32_t n_nodes, const uint64_t *seg_off,
+                    uint32_t n_rails, uint32_t rail, const uint32_t *seg_ids, uint32_t n_segs,
+                    uint32_t elem_bytes, void *const *node_bufs, void *stream)
+{
+    return segment_copy(send_bufs, node_bufs, n_nodes, seg_off, n_rails, rail, seg_ids, n_segs,
+                        elem_bytes, false, 0, nullptr, static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

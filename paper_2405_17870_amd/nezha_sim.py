@@ -1,0 +1,182 @@
+"""Thin binding over the C-ABI library ``libnezha_sim.so`` (see include/nezha_sim.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP
+kernels (or, for the two index maps, in its host C++).  PyTorch is used for
+device memory and streams.  There is no fallback: if the library has not been
+built or cannot be loaded, the first call raises.
+
+Function names and argument order follow the C header; each docstring cites
+the passage of Nezha (arXiv 2405.17870) that defines the operation.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnezha_sim.so")
+
+NZ_MAX_NODES = 128
+NZ_MAX_RAILS = 8
+
+NZ_F32, NZ_BF16, NZ_F16, NZ_I32 = 0, 1, 2, 3
+NZ_RING_STEPWISE, NZ_FUSED = 0, 1
+
+DTYPE_CODE = {"f32": NZ_F32, "bf16": NZ_BF16, "f16": NZ_F16, "i32": NZ_I32}
+MODE_CODE = {"ring-stepwise": NZ_RING_STEPWISE, "ring": NZ_RING_STEPWISE, "fused": NZ_FUSED}
+ELEM_BYTES = {"f32": 4, "bf16": 2, "f16": 2, "i32": 4}
+
+EXPORTS = [
+    "nz_status_str", "nz_last_hip_error", "nz_dtype_bytes", "nz_rail_partition",
+    "nz_rail_partition_ex", "nz_segment_map", "nz_allreduce_sim", "nz_pack", "nz_unpack",
+]
+
+
+class NezhaSimError(RuntimeError):
+    """A library call returned a status other than NZ_OK."""
+
+    def __init__(self, status: int, text: str):
+        super().__init__(f"nezha_sim: status {status}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def load() -> ctypes.CDLL:
+    """Load ``libnezha_sim.so``; raises if it is missing (no fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it first (python -m paper_2405_17870_amd.build "
+            "or __graft_entry__.build()); there is no fallback path")
+    import torch  # noqa: F401  -- loads the HIP runtime this library must share with torch
+    lib = ctypes.CDLL(LIB_PATH)
+    u64, u32, vp, i32 = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_int
+    lib.nz_status_str.argtypes = [i32]
+    lib.nz_status_str.restype = ctypes.c_char_p
+    lib.nz_last_hip_error.argtypes = []
+    lib.nz_last_hip_error.restype = ctypes.c_char_p
+    lib.nz_dtype_bytes.argtypes = [i32]
+    lib.nz_dtype_bytes.restype = u32
+    lib.nz_rail_partition.argtypes = [u64, u32, vp, u32, vp]
+    lib.nz_rail_partition_ex.argtypes = [u64, u32, u32, vp, u32, vp]
+    lib.nz_segment_map.argtypes = [vp, u32, u32, vp]
+    lib.nz_allreduce_sim.argtypes = [vp, u32, u64, vp, u32, i32, i32, vp, vp]
+    lib.nz_pack.argtypes = [vp, u32, vp, u32, u32, vp, u32, u32, vp, u64, vp, vp]
+    lib.nz_unpack.argtypes = [vp, u32, vp, u32, u32, vp, u32, u32, vp, vp]
+    for name in ("nz_rail_partition", "nz_rail_partition_ex", "nz_segment_map",
+                 "nz_allreduce_sim", "nz_pack", "nz_unpack"):
+        getattr(lib, name).restype = i32
+    lib.nz_set_fused_tile_iters.argtypes = [i32]
+    lib.nz_set_fused_tile_iters.restype = None
+    _lib = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status != 0:
+        lib = load()
+        text = lib.nz_status_str(status).decode()
+        hip = lib.nz_last_hip_error().decode()
+        raise NezhaSimError(status, text + (f" ({hip})" if status == 5 and hip else ""))
+
+
+def _u32_array(values: Sequence[int]):
+    vals = [int(v) for v in values]
+    for v in vals:
+        if v < 0 or v > 0xFFFFFFFF:
+            raise ValueError("value does not fit an unsigned 32-bit integer")
+    return (ctypes.c_uint32 * max(len(vals), 1))(*vals)
+
+
+def _ptr_array(tensors) -> ctypes.Array:
+    arr = (ctypes.c_void_p * max(len(tensors), 1))()
+    for i, t in enumerate(tensors):
+        arr[i] = t.data_ptr() if hasattr(t, "data_ptr") else int(t)
+    return arr
+
+
+def _stream_handle(stream) -> ctypes.c_void_p:
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def nz_rail_partition(n_elems: int, elem_bytes: int, ratios: Sequence[int],
+                      align_bytes: Optional[int] = None) -> np.ndarray:
+    """Rail boundaries in elements, ``n_rails + 1`` entries (Sec. 3.4, 3.5; shares sum to
+    one, Sec. 4.3 under Eq. 5).  ``align_bytes=None`` is the library's fixed 256 bytes."""
+    lib = load()
+    w = _u32_array(ratios)
+    out = np.zeros(len(ratios) + 1, dtype=np.uint64)
+    if align_bytes is None:
+        _check(lib.nz_rail_partition(n_elems, elem_bytes, w, len(ratios), out.ctypes.data))
+    else:
+        _check(lib.nz_rail_partition_ex(n_elems, elem_bytes, align_bytes, w, len(ratios),
+                                        out.ctypes.data))
+    return out
+
+
+def nz_segment_map(rail_off: Sequence[int], n_nodes: int) -> np.ndarray:
+    """Ring segments of every rail, shape ``[n_rails, n_nodes + 1]`` (Sec. 2.1.1, Eq. 1)."""
+    lib = load()
+    b = np.ascontiguousarray(rail_off, dtype=np.uint64)
+    n_rails = len(b) - 1
+    seg = np.zeros((max(n_rails, 0), n_nodes + 1), dtype=np.uint64)
+    _check(lib.nz_segment_map(b.ctypes.data, n_rails, n_nodes, seg.ctypes.data))
+    return seg
+
+
+def nz_allreduce_sim(node_bufs: Sequence, n_elems: int, ratios: Sequence[int], dtype: str,
+                     mode: str, out_bufs: Sequence, stream=None) -> None:
+    """Sum of the nodes' buffers into every output buffer (Sec. 4.2 aggregation phase; ring
+    schedule of Sec. 2.1.1 / Eq. 1; rails per Sec. 4.1).  Asynchronous on ``stream``
+    (default: torch's current stream).  Buffers are torch tensors or raw device addresses."""
+    lib = load()
+    if len(out_bufs) != len(node_bufs):
+        raise ValueError("out_bufs must have one entry per node")
+    _check(lib.nz_allreduce_sim(_ptr_array(node_bufs), len(node_bufs), n_elems,
+                                _u32_array(ratios), len(ratios), DTYPE_CODE[dtype],
+                                MODE_CODE[mode], _ptr_array(out_bufs), _stream_handle(stream)))
+
+
+def nz_pack(node_bufs: Sequence, seg_off: np.ndarray, rail: int, seg_ids: Sequence[int],
+            elem_bytes: int, send_bufs: Sequence, send_capacity_bytes: int, stream=None) -> int:
+    """Stage the listed segments of one rail into contiguous send buffers, all nodes at once
+    (Sec. 3.2: UnboundBuffer to the rail's Buffer).  Returns the packed bytes per node."""
+    lib = load()
+    seg = np.ascontiguousarray(seg_off, dtype=np.uint64)
+    n_rails, n_nodes = seg.shape[0], seg.shape[1] - 1
+    if len(node_bufs) != n_nodes or len(send_bufs) != n_nodes:
+        raise ValueError("one node buffer and one send buffer per node")
+    packed = ctypes.c_uint64(0)
+    _check(lib.nz_pack(_ptr_array(node_bufs), n_nodes, seg.ctypes.data, n_rails, rail,
+                       _u32_array(seg_ids), len(seg_ids), elem_bytes, _ptr_array(send_bufs),
+                       send_capacity_bytes, ctypes.byref(packed), _stream_handle(stream)))
+    return int(packed.value)
+
+
+def nz_unpack(send_bufs: Sequence, seg_off: np.ndarray, rail: int, seg_ids: Sequence[int],
+              elem_bytes: int, node_bufs: Sequence, stream=None) -> None:
+    """Scatter contiguous send buffers back into the listed segments (Sec. 3.2: results
+    return from the rail's Buffer to the UnboundBuffer)."""
+    lib = load()
+    seg = np.ascontiguousarray(seg_off, dtype=np.uint64)
+    n_rails, n_nodes = seg.shape[0], seg.shape[1] - 1
+    if len(node_bufs) != n_nodes or len(send_bufs) != n_nodes:
+        raise ValueError("one node buffer and one send buffer per node")
+    _check(lib.nz_unpack(_ptr_array(send_bufs), n_nodes, seg.ctypes.data, n_rails, rail,
+                         _u32_array(seg_ids), len(seg_ids), elem_bytes, _ptr_array(node_bufs),
+                         _stream_handle(stream)))
+
+
+def set_fused_tile_iters(iters: int) -> None:
+    """Tuning hook: 256-vector sub-tiles per workgroup of the fused kernel (1, 2 or 4)."""
+    load().nz_set_fused_tile_iters(int(iters))

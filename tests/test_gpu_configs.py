@@ -1,0 +1,133 @@
+"""GPU parity at the five benchmark shapes, in the launch configuration the benchmark times.
+
+c1, c2, c3 and c5 are compared element by element at full size; c4 (21 GB of inputs) on
+sampled element ranges the oracle computes one by one (both ends, the rail boundary, segment
+boundaries, random ranges) plus properties that hold at any size (all nodes bitwise identical;
+the packed route gives bitwise the same sums).  Inputs are synthetic gradients of the shapes'
+sizes (see paper_2405_17870_amd/inputs.py)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2405_17870_amd import inputs
+from paper_2405_17870_amd import nezha_sim as nz
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(*a):
+    print(*a, flush=True)
+
+
+def _run(w, mode, ins):
+    outs = [torch.empty_like(t) for t in ins]
+    nz.nz_allreduce_sim(ins, w.n_elems, w.ratios, w.dtype, mode, outs)
+    torch.cuda.synchronize()
+    return outs
+
+
+def _all_equal(outs):
+    return all(torch.equal(outs[0], o) for o in outs[1:])
+
+
+@pytest.mark.parametrize("name", ["c1", "c1_i32", "c2"])
+def test_full_compare_both_modes(orc, name):
+    w = inputs.WORKLOADS[name]
+    _say(f"{name}: generating")
+    ins = inputs.workload_buffers(w, device=gu.DEV)
+    host = [inputs.to_host_storage(t) for t in ins]
+    _say(f"{name}: fused")
+    outs = _run(w, "fused", ins)
+    assert _all_equal(outs)
+    gu.check_fused_against_oracle(orc, w.dtype, inputs.to_host_storage(outs[0]), host, name)
+    _say(f"{name}: ring-stepwise")
+    outs = _run(w, "ring-stepwise", ins)
+    seg = orc.segment_map(orc.rail_partition(w.n_elems, w.ratios, 4), w.n_nodes)
+    want, sent = orc.ring_allreduce(gu.ORC_CODE[w.dtype], host, seg)
+    assert int(sent.sum()) == 2 * (w.n_nodes - 1) * w.payload_bytes          # Eq. 1
+    for i in range(w.n_nodes):
+        gu.assert_same_bits(inputs.to_host_storage(outs[i]), want[i], w.dtype, f"{name} ring node {i}")
+    gu.check_fused_against_oracle(orc, w.dtype, inputs.to_host_storage(outs[0]), host, name + " ring")
+
+
+def test_c3_bf16_outliers_full_compare(orc):
+    w = inputs.WORKLOADS["c3"]
+    _say("c3: generating")
+    ins = inputs.workload_buffers(w, device=gu.DEV)
+    outs = _run(w, "fused", ins)
+    assert _all_equal(outs)
+    _say("c3: oracle")
+    host = [inputs.to_host_storage(t) for t in ins]
+    n_escape = gu.check_fused_against_oracle(orc, "bf16", inputs.to_host_storage(outs[0]), host, "c3")
+    _say(f"c3: elements judged by the cancellation clause: {n_escape} of {w.n_elems}")
+    assert n_escape <= w.n_elems // 1_000_000
+
+
+def _ranges_c4(w, orc, rng):
+    b = orc.rail_partition(w.n_elems, w.ratios, 2)
+    seg = orc.segment_map(b, w.n_nodes)
+    pts = [0, w.n_elems, int(b[1]), int(seg[0, 1]), int(seg[0, 17]), int(seg[1, 1]), int(seg[1, 5]),
+           int(seg[1, 31])]
+    pts += [int(x) for x in rng.integers(0, w.n_elems, size=6)]
+    half = 40_000
+    return [(max(0, p - half), min(w.n_elems, p + half)) for p in pts]
+
+
+def test_c4_sampled_ranges_and_packed_route(orc):
+    w = inputs.WORKLOADS["c4"]
+    N, n = w.n_nodes, w.n_elems
+    _say("c4: generating 32 x 335M bf16")
+    ins = inputs.workload_buffers(w, device=gu.DEV)
+    _say("c4: fused")
+    outs = _run(w, "fused", ins)
+    assert _all_equal(outs)
+    rng = np.random.default_rng(4)
+    escapes = 0
+    for lo, hi in _ranges_c4(w, orc, rng):
+        host = [inputs.to_host_storage(t[lo:hi]) for t in ins]
+        escapes += gu.check_fused_against_oracle(orc, "bf16", inputs.to_host_storage(outs[0][lo:hi]),
+                                                 host, f"c4[{lo}:{hi}]")
+    _say(f"c4: sampled ranges ok, cancellation clause used for {escapes} elements")
+    assert escapes <= 2
+
+    # pack every rail, allreduce the packed buffers, unpack: bitwise the same sums
+    _say("c4: packed route")
+    b = nz.nz_rail_partition(n, 2, w.ratios)
+    seg = nz.nz_segment_map(b, N)
+    routed = [torch.zeros_like(t) for t in ins]
+    ids = list(range(N))
+    for rail in range(len(w.ratios)):
+        L = int(b[rail + 1] - b[rail])
+        send = [torch.empty(L, dtype=torch.bfloat16, device=gu.DEV) for _ in range(N)]
+        assert nz.nz_pack(ins, seg, rail, ids, 2, send, L * 2) == L * 2
+        nz.nz_allreduce_sim(send, L, (1,), "bf16", "fused", send)
+        nz.nz_unpack(send, seg, rail, ids, 2, routed)
+        torch.cuda.synchronize()
+        del send
+    for i in range(N):
+        assert torch.equal(routed[i], outs[0]), i
+
+
+def test_c5_128_nodes_full_compare(orc):
+    w = inputs.WORKLOADS["c5"]
+    _say("c5: generating 128 x 16.7M fp32")
+    ins = inputs.workload_buffers(w, device=gu.DEV)
+    host = [inputs.to_host_storage(t) for t in ins]
+    _say("c5: fused")
+    outs = _run(w, "fused", ins)
+    assert _all_equal(outs)
+    gu.check_fused_against_oracle(orc, "f32", inputs.to_host_storage(outs[0]), host, "c5 fused")
+    _say("c5: ring-stepwise")
+    outs = _run(w, "ring-stepwise", ins)
+    assert _all_equal(outs)
+    got = inputs.to_host_storage(outs[0])
+    del outs
+    _say("c5: oracle ring (254 steps on the host)")
+    seg = orc.segment_map(orc.rail_partition(w.n_elems, w.ratios, 4), w.n_nodes)
+    want, sent = orc.ring_allreduce(orc.F32, host, seg)
+    assert int(sent.sum()) == 2 * (w.n_nodes - 1) * w.payload_bytes
+    gu.assert_same_bits(got, want[0], "f32", "c5 ring")
+    assert all(np.array_equal(want[0], x) for x in want[1:8])
+    gu.check_fused_against_oracle(orc, "f32", got, host, "c5 ring vs sum")

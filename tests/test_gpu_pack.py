@@ -1,0 +1,101 @@
+"""GPU parity of nz_pack / nz_unpack against the CPU oracle, through the C-ABI."""
+import random
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2405_17870_amd import inputs
+from paper_2405_17870_amd import nezha_sim as nz
+
+import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+def _case(orc, N, ratios, n, e, rail, ids, capacity_slack=64):
+    print(f"pack N={N} ratios={ratios} n={n} e={e} rail={rail} n_ids={len(ids)}", flush=True)
+    dtype = "f32" if e == 4 else "bf16"
+    seg = nz.nz_segment_map(nz.nz_rail_partition(n, e, ratios), N)
+    assert np.array_equal(seg, orc.segment_map(orc.rail_partition(n, ratios, e), N))
+    rng = np.random.default_rng(n + N)
+    host = [rng.integers(0, 256, size=n * e, dtype=np.uint8) for _ in range(N)]
+    node = [gu.Guarded(n, dtype) for _ in range(N)]
+    for g, h in zip(node, host):
+        g.t.view(torch.uint8).copy_(torch.from_numpy(h))
+    total = sum(int(seg[rail, j + 1] - seg[rail, j]) for j in ids) * e
+    cap_elems = max((total + capacity_slack) // e, 1)     # torch gives empty tensors a null address
+    send = [gu.Guarded(cap_elems, dtype, canary=0x77) for _ in range(N)]
+    for s in send:
+        s.t.view(torch.uint8).fill_(0xEE)
+    packed = nz.nz_pack([g.t for g in node], seg, rail, ids, e, [s.t for s in send], cap_elems * e)
+    torch.cuda.synchronize()
+    assert packed == total
+    for m in range(N):
+        want, nbytes = orc.pack(host[m], seg, rail, ids, e)
+        got = send[m].t.view(torch.uint8).cpu().numpy()
+        assert nbytes == total and np.array_equal(got[:total], want)
+        assert (got[total:] == 0xEE).all()                       # nothing past the packed bytes
+        assert send[m].guards_intact() and node[m].guards_intact()
+        assert np.array_equal(node[m].t.view(torch.uint8).cpu().numpy(), host[m])
+    # unpack into canary-filled node buffers (unique ids only)
+    uniq = list(dict.fromkeys(ids))
+    send_u = [gu.Guarded(cap_elems, dtype) for _ in range(N)]
+    nz.nz_pack([g.t for g in node], seg, rail, uniq, e, [s.t for s in send_u], cap_elems * e)
+    dst = [gu.Guarded(n, dtype) for _ in range(N)]
+    for d in dst:
+        d.t.view(torch.uint8).fill_(0xA5)
+    nz.nz_unpack([s.t for s in send_u], seg, rail, uniq, e, [d.t for d in dst])
+    torch.cuda.synchronize()
+    for m in range(N):
+        want = np.full(n * e, 0xA5, dtype=np.uint8)
+        pk, _ = orc.pack(host[m], seg, rail, uniq, e)
+        orc.unpack(pk, seg, rail, uniq, e, want)
+        assert np.array_equal(dst[m].t.view(torch.uint8).cpu().numpy(), want)
+        assert dst[m].guards_intact()
+
+
+@pytest.mark.parametrize("e", [2, 4])
+def test_pack_unpack_whole_rail_and_ring_order(orc, e):
+    for N, ratios, n in [(3, (3, 1), 200), (8, (100, 40), 70_001), (8, (100, 100, 40), 123_457),
+                         (32, (100, 25), 400_003), (128, (100, 100, 40, 10), 300_007), (1, (1,), 5000)]:
+        R = len(ratios)
+        for rail in range(R):
+            _case(orc, N, ratios, n, e, rail, list(range(N)))                       # whole rail
+        r = N // 2
+        _case(orc, N, ratios, n, e, R - 1, [(r - s) % N for s in range(N)])         # order node r sends in
+        _case(orc, N, ratios, n, e, 0, [(r - s) % N for s in range(min(N, 5))])
+
+
+@pytest.mark.parametrize("e", [2, 4])
+def test_pack_unpack_random_lists(orc, e):
+    rnd = random.Random(100 + e)
+    for _ in range(25):
+        N = rnd.choice([1, 2, 3, 5, 8, 17, 64, 128])
+        R = rnd.randint(1, 4)
+        ratios = [rnd.randint(0, 100) + (k == 0) for k in range(R)]
+        n = rnd.choice([rnd.randint(0, 300), rnd.randint(1000, 200_000)])
+        ids = [rnd.randrange(N) for _ in range(rnd.randint(0, min(N, 20)))]
+        _case(orc, N, ratios, n, e, rnd.randrange(R), ids, capacity_slack=rnd.choice([0, 2 * e, 640]))
+
+
+def test_pack_errors(orc):
+    N, n, e = 4, 10_000, 4
+    seg = nz.nz_segment_map(nz.nz_rail_partition(n, e, (1, 1)), N)
+    node = [gu.Guarded(n, "f32") for _ in range(N)]
+    send = [gu.Guarded(n, "f32") for _ in range(N)]
+
+    def status(fn, *a):
+        with pytest.raises(nz.NezhaSimError) as ex:
+            fn(*a)
+        return ex.value.status
+
+    nt, st = [g.t for g in node], [g.t for g in send]
+    assert status(nz.nz_pack, nt, seg, 0, [0, 1, 2, 3], e, st, 100) == 4             # capacity
+    assert status(nz.nz_pack, nt, seg, 2, [0], e, st, n * e) == 1                    # rail out of range
+    assert status(nz.nz_pack, nt, seg, 0, [4], e, st, n * e) == 1                    # segment id out of range
+    assert status(nz.nz_unpack, st, seg, 0, [1, 1], e, nt) == 1                      # repeated id in unpack
+    assert status(nz.nz_pack, nt, seg, 0, [0], e, nt, n * e) == 3                    # source == destination
+    assert status(nz.nz_pack, nt, seg, 0, [0], 3, st, n * e) == 1
+    torch.cuda.synchronize()
+    assert all(g.guards_intact() for g in node + send)

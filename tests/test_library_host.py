@@ -1,0 +1,74 @@
+"""CPU-only checks of the C-ABI library: it loads, exports what the header declares, and its
+host-side index maps agree bit for bit with the oracle (no GPU call is made here)."""
+import ctypes
+import os
+import random
+import re
+
+import numpy as np
+import pytest
+
+from paper_2405_17870_amd import nezha_sim as nz
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "nezha_sim.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(nz_[a-z0-9_]+)\s*\(", header))
+    assert {"nz_rail_partition", "nz_allreduce_sim", "nz_pack", "nz_unpack"} <= declared
+    lib = nz.load()
+    for name in sorted(declared):
+        assert hasattr(lib, name), name
+    assert set(nz.EXPORTS) == declared
+
+
+def test_status_strings_and_dtype_sizes():
+    lib = nz.load()
+    assert lib.nz_status_str(0) == b"ok"
+    assert all(lib.nz_status_str(s) for s in range(6))
+    assert [lib.nz_dtype_bytes(d) for d in range(5)] == [4, 2, 2, 4, 0]
+
+
+def test_partition_matches_oracle_bit_for_bit(orc):
+    rnd = random.Random(2024)
+    cases = [(1_048_576, 4, [100, 40]), (25_557_032, 4, [100, 40]),
+             (138_357_544, 2, [100, 100, 40]), (335_000_000, 2, [100, 25]),
+             (16_777_216, 4, [100, 100, 40, 10]), (200, 4, [3, 1]), (1000, 4, [1, 0]),
+             (1000, 2, [0, 0, 5, 0]), (0, 4, [1, 1])]
+    for _ in range(500):
+        R = rnd.randint(1, 8)
+        w = [rnd.choice([0, 1, rnd.randint(0, 200), rnd.randint(0, 2**32 - 1)]) for _ in range(R)]
+        if sum(w) == 0:
+            w[rnd.randrange(R)] = 3
+        cases.append((rnd.choice([rnd.randint(0, 5000), rnd.randint(0, 2**34), rnd.randint(0, 2**60)]),
+                      rnd.choice([2, 4]), w))
+    for n, e, w in cases:
+        assert nz.nz_rail_partition(n, e, w).tolist() == orc.rail_partition(n, w, e).tolist()
+        a = rnd.choice([e, 16, 64, 512])
+        assert nz.nz_rail_partition(n, e, w, a).tolist() == orc.rail_partition(n, w, e, a).tolist()
+
+
+def test_segment_map_matches_oracle_bit_for_bit(orc):
+    rnd = random.Random(5)
+    for _ in range(300):
+        R = rnd.randint(1, 8)
+        N = rnd.choice([1, 2, 3, 8, 32, 128, rnd.randint(1, 128)])
+        b = sorted(rnd.randint(0, 10**rnd.randint(1, 12)) for _ in range(R + 1))
+        assert (nz.nz_segment_map(b, N) == orc.segment_map(b, N)).all()
+
+
+def test_host_entry_points_reject_bad_arguments():
+    with pytest.raises(nz.NezhaSimError) as e:
+        nz.nz_rail_partition(100, 4, [0, 0])
+    assert e.value.status == 1
+    with pytest.raises(nz.NezhaSimError):
+        nz.nz_rail_partition(100, 3, [1])
+    with pytest.raises(nz.NezhaSimError):
+        nz.nz_rail_partition(100, 4, [1], align_bytes=6)
+    with pytest.raises(nz.NezhaSimError):
+        nz.nz_segment_map([0, 10, 5], 4)
+    lib = nz.load()
+    assert lib.nz_rail_partition(10, 4, None, 1, None) == 1
+    assert lib.nz_segment_map(None, 1, 1, None) == 1
