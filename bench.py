@@ -1,0 +1,232 @@
+#!/usr/bin/env python3
+"""Benchmark of the allreduce reduction engine on one MI355X.
+
+One "step" is one pass of the whole path over one batch of synthetic gradients
+already resident in HBM:
+
+  1. nz_allreduce_sim, fused mode         (rail partition + segment cut + N-way reduce/broadcast)
+  2. nz_allreduce_sim, ring-stepwise mode (the same sums as 2(N-1) ring steps)
+  3. nz_pack of every rail, all nodes     (node buffers -> contiguous send buffers)
+  4. nz_unpack of every rail, all nodes   (send buffers -> node buffers)
+
+The reported value is effective HBM throughput of the step: the bytes the method itself must
+move (fused (N+K)*S, ring-stepwise 5(N-1)*S, pack 2*N*S, unpack 2*N*S; S = payload bytes per
+node, K = distinct output buffers = N) divided by the step time.  Per-part times come from HIP
+events on the stream the kernels run on; `roofline` describes the fused kernel.
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import hashlib
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
+
+
+def parse_args():
+    p = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=10)
+    p.add_argument("--warmup", type=int, default=2)
+    p.add_argument("--workload", default="c4", help="c1, c1_i32, c2, c3, c4 (default), c5")
+    p.add_argument("--parts", default="fused,ring,pack,unpack",
+                   help="comma list of parts to run in a step (default: all four)")
+    p.add_argument("--no-cpu-baseline", action="store_true")
+    p.add_argument("--fused-iters", type=int, default=0, help="tuning: sub-tiles per workgroup")
+    p.add_argument("--cpu-sample-elems", type=int, default=8 * 1024 * 1024)
+    return p.parse_args()
+
+
+def recorded_traffic(kind: str):
+    """HBM bytes per launch from the committed counter runs, or None if the kernel source has
+    changed since they were taken."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    src = os.path.join(ROOT, "paper_2405_17870_amd", "csrc", "nz_kernels.hip")
+    try:
+        rec = json.load(open(path))
+        digest = hashlib.sha256(open(src, "rb").read()).hexdigest()
+        if rec.get("kernel_source_sha256") != digest:
+            return None
+        return rec.get(kind)
+    except (OSError, ValueError):
+        return None
+
+
+def cpu_baseline(w, n_sample: int, parts):
+    """The oracle, as it stands, on a bounded slice of the same workload (same node count,
+    same ratios, n_sample elements per node)."""
+    import numpy as np
+    import oracle as orc
+    from paper_2405_17870_amd import inputs
+
+    code = {"f32": orc.F32, "bf16": orc.BF16, "f16": orc.F16, "i32": orc.I32}[w.dtype]
+    e = inputs.ELEM_BYTES[w.dtype]
+    N = w.n_nodes
+    n = min(n_sample, w.n_elems)
+    host = [inputs.to_host_storage(t) for t in inputs.workload_buffers(w, device="cpu", n_elems=n)]
+    S = n * e
+    seg = orc.segment_map(orc.rail_partition(n, w.ratios, e), N)
+    bytes_done = 0
+    t0 = time.perf_counter()
+    if "fused" in parts:
+        if w.dtype == "i32":
+            orc.sum_i32(host)
+        else:
+            s, _ = orc.sum_float(code, host)
+            orc.round_to_storage(code, s)
+        bytes_done += 2 * N * S
+    if "ring" in parts:
+        orc.ring_allreduce(code, host, seg)
+        bytes_done += 5 * (N - 1) * S
+    if "pack" in parts or "unpack" in parts:
+        ids = list(range(N))
+        for rail in range(len(w.ratios)):
+            for m in range(N):
+                buf, _ = orc.pack(host[m], seg, rail, ids, e)
+                if "pack" in parts:
+                    bytes_done += 2 * buf.size
+                if "unpack" in parts:
+                    orc.unpack(buf, seg, rail, ids, e, host[m])
+                    bytes_done += 2 * buf.size
+    dt = time.perf_counter() - t0
+    return {
+        "value": round(bytes_done / dt / 1e9, 3), "unit": "GB/s", "cores": orc.threads(),
+        "kind": "oracle", "seconds": round(dt, 3),
+        "sample": (f"same step ({'+'.join(parts)}) on the first {n} elements of each of the "
+                   f"{N} nodes of {w.name}; the definitional sum runs on {orc.threads()} OpenMP "
+                   "threads, the ring emulation and pack/unpack on one"),
+    }
+
+
+def main() -> int:
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the N simulated nodes share one "
+              "MI355X's HBM); --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2405_17870_amd import inputs
+    from paper_2405_17870_amd import nezha_sim as nz
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    nz.load()
+    if args.fused_iters:
+        nz.set_fused_tile_iters(args.fused_iters)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = inputs.WORKLOADS[args.workload]
+    parts = [p for p in args.parts.split(",") if p]
+    N, n, e = w.n_nodes, w.n_elems, inputs.ELEM_BYTES[w.dtype]
+    S = n * e
+    R = len(w.ratios)
+
+    ins = inputs.workload_buffers(w, device=dev)
+    outs = [torch.empty_like(t) for t in ins]
+    rail_off = nz.nz_rail_partition(n, e, w.ratios)
+    seg = nz.nz_segment_map(rail_off, N)
+    send = []
+    if "pack" in parts or "unpack" in parts:
+        for k in range(R):
+            L = int(rail_off[k + 1] - rail_off[k])
+            send.append([torch.zeros(max(L, 1), dtype=ins[0].dtype, device=dev) for _ in range(N)])
+    ids = list(range(N))
+    torch.cuda.synchronize()
+
+    alg_bytes = {"fused": 2 * N * S, "ring": 5 * (N - 1) * S, "pack": 2 * N * S, "unpack": 2 * N * S}
+
+    def run_part(p):
+        if p == "fused":
+            nz.nz_allreduce_sim(ins, n, w.ratios, w.dtype, "fused", outs)
+        elif p == "ring":
+            nz.nz_allreduce_sim(ins, n, w.ratios, w.dtype, "ring-stepwise", outs)
+        elif p == "pack":
+            for k in range(R):
+                nz.nz_pack(ins, seg, k, ids, e, send[k], send[k][0].numel() * e)
+        elif p == "unpack":
+            for k in range(R):
+                nz.nz_unpack(send[k], seg, k, ids, e, outs)
+        else:
+            raise SystemExit(f"unknown part {p!r}")
+
+    def step(events=None):
+        for p in parts:
+            if events is not None:
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                run_part(p)
+                b.record()
+                events[p].append((a, b))
+            else:
+                run_part(p)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = {p: [] for p in parts}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_per_step = wall * 1e3 / args.steps
+    step_bytes = sum(alg_bytes[p] for p in parts)
+    part_stats = {}
+    for p in parts:
+        ms = sum(a.elapsed_time(b) for a, b in events[p]) / len(events[p])
+        gbs = alg_bytes[p] / (ms * 1e-3) / 1e9
+        part_stats[p] = {"ms": round(ms, 4), "payload_GBps": round(S / (ms * 1e-3) / 1e9, 2),
+                         "hbm_GBps": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
+                         "algorithmic_bytes": alg_bytes[p]}
+
+    head = "fused" if "fused" in parts else parts[0]
+    launches = {"fused": 1, "ring": 2 * (N - 1), "pack": R, "unpack": R}[head]
+    achieved = part_stats[head]["hbm_GBps"]
+    roofline = {
+        "kernel": {"fused": "nz_fused_reduce_bcast", "ring": "nz_ring_step",
+                   "pack": "nz_segment_copy", "unpack": "nz_segment_copy"}[head],
+        "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "algorithmic_bytes_per_launch": alg_bytes[head] // launches,
+        "avg_launch_ms": round(part_stats[head]["ms"] / launches, 4),
+        "traffic": recorded_traffic(f"{head}_{w.name}"),
+    }
+
+    out = {
+        "metric": "allreduce-sim effective GB/s and % of HBM peak, fused vs ring-stepwise",
+        "value": round(step_bytes / (ms_per_step * 1e-3) / 1e9, 1),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "i32" if w.dtype == "i32" else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: {N} simulated nodes x {n} {w.dtype} elements, "
+                               f"rails {':'.join(map(str, w.ratios))}",
+                   "storage_dtype": w.dtype, "n_nodes": N, "n_elems": n, "ratios": list(w.ratios),
+                   "parts": parts, "distinct_outputs": N},
+        "pct_of_hbm_peak": round(100.0 * step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
+        "parts": part_stats,
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        del ins, outs, send
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_elems, parts)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
