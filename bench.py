@@ -41,7 +41,12 @@ def parse_args():
     p.add_argument("--parts", default="fused,ring,pack,unpack",
                    help="comma list of parts to run in a step (default: all four)")
     p.add_argument("--no-cpu-baseline", action="store_true")
-    p.add_argument("--fused-iters", type=int, default=0, help="tuning: sub-tiles per workgroup")
+    p.add_argument("--placement", default="spread", choices=["spread", "packed", "torch"],
+                   help="where the buffers live in HBM: spread = inputs in the first 96 GiB region, "
+                        "written buffers striped over all three regions (default); packed = all in the "
+                        "first region; torch = plain torch allocations")
+    p.add_argument("--packed-offset-gib", type=float, default=0.0,
+                   help="with --placement packed: arena offset at which the buffers start")
     p.add_argument("--cpu-sample-elems", type=int, default=8 * 1024 * 1024)
     return p.parse_args()
 
@@ -117,13 +122,12 @@ def main() -> int:
     import torch
     from paper_2405_17870_amd import inputs
     from paper_2405_17870_amd import nezha_sim as nz
+    from paper_2405_17870_amd import placement
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
     nz.load()
-    if args.fused_iters:
-        nz.set_fused_tile_iters(args.fused_iters)
     dev = "cuda:0"
     torch.cuda.set_device(0)
     w = inputs.WORKLOADS[args.workload]
@@ -132,15 +136,38 @@ def main() -> int:
     S = n * e
     R = len(w.ratios)
 
-    ins = inputs.workload_buffers(w, device=dev)
-    outs = [torch.empty_like(t) for t in ins]
+    tdtype = inputs.TORCH_DTYPE[w.dtype]
     rail_off = nz.nz_rail_partition(n, e, w.ratios)
     seg = nz.nz_segment_map(rail_off, N)
-    send = []
-    if "pack" in parts or "unpack" in parts:
-        for k in range(R):
-            L = int(rail_off[k + 1] - rail_off[k])
-            send.append([torch.zeros(max(L, 1), dtype=ins[0].dtype, device=dev) for _ in range(N)])
+    need_send = "pack" in parts or "unpack" in parts
+    rail_len = [max(int(rail_off[k + 1] - rail_off[k]), 1) for k in range(R)]
+    placement_note = "plain torch allocations"
+    arena = placement.try_arena(dev) if args.placement != "torch" else None
+    packed_ref_outs = None
+    if arena is not None:
+        written = (0, 1, 2) if args.placement == "spread" else (0,)
+        if args.placement == "packed" and args.packed_offset_gib > 0:
+            arena.set_cursor(0, int(args.packed_offset_gib * (1 << 30)))
+        ins = [arena.alloc(n, tdtype, 0) for _ in range(N)]
+        outs = arena.alloc_striped(N, n, tdtype, written)
+        send = [arena.alloc_striped(N, rail_len[k], tdtype, written, start=k) for k in range(R)] \
+            if need_send else []
+        if args.placement == "spread" and "fused" in parts and arena.free_in(0) >= N * (n * e + (2 << 20)):
+            packed_ref_outs = [arena.alloc(n, tdtype, 0) for _ in range(N)]
+        placement_note = ("inputs in the first 96 GiB HBM region; outputs and send buffers striped over "
+                          "the three 96 GiB regions" if args.placement == "spread"
+                          else f"all buffers back to back from arena offset {args.packed_offset_gib:g} GiB")
+        for i in range(N):
+            ins[i].copy_(inputs.node_buffer(w.dtype, n, w.seed, i, device=dev, std=w.std,
+                                            outlier_frac=w.outlier_frac, outlier_scale=w.outlier_scale))
+        for group in send:
+            for t in group:
+                t.zero_()
+    else:
+        ins = inputs.workload_buffers(w, device=dev)
+        outs = [torch.empty_like(t) for t in ins]
+        send = [[torch.zeros(rail_len[k], dtype=tdtype, device=dev) for _ in range(N)] for k in range(R)] \
+            if need_send else []
     ids = list(range(N))
     torch.cuda.synchronize()
 
@@ -215,13 +242,27 @@ def main() -> int:
         "config": {"workload": f"{w.name}: {N} simulated nodes x {n} {w.dtype} elements, "
                                f"rails {':'.join(map(str, w.ratios))}",
                    "storage_dtype": w.dtype, "n_nodes": N, "n_elems": n, "ratios": list(w.ratios),
-                   "parts": parts, "distinct_outputs": N},
+                   "parts": parts, "distinct_outputs": N, "placement": placement_note},
         "pct_of_hbm_peak": round(100.0 * step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
         "parts": part_stats,
         "roofline": roofline,
     }
+    if packed_ref_outs is not None:
+        # The same fused call with its outputs in the inputs' region, for reference.
+        ev = []
+        for i in range(5):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            nz.nz_allreduce_sim(ins, n, w.ratios, w.dtype, "fused", packed_ref_outs)
+            b.record()
+            ev.append((a, b))
+        torch.cuda.synchronize()
+        ms = sum(a.elapsed_time(b) for a, b in ev[1:]) / (len(ev) - 1)
+        out["fused_with_outputs_in_one_region"] = {
+            "ms": round(ms, 4), "hbm_GBps": round(alg_bytes["fused"] / (ms * 1e-3) / 1e9, 1),
+            "frac_of_peak": round(alg_bytes["fused"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
     if not args.no_cpu_baseline:
-        del ins, outs, send
+        del ins, outs, send, packed_ref_outs, arena
         torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_elems, parts)
     print(json.dumps(out), flush=True)

@@ -34,6 +34,19 @@ typedef uint64_t u64;
 
 constexpr int kThreads = 256;  // four wave64 per workgroup
 
+// Kernel-argument blocks are read where they already are: in the kernarg
+// segment (constant address space), through scalar loads, with no private copy
+// even when a table in them is indexed with a run-time value.  Each kernel has
+// its argument struct as its only parameter, so the struct starts the segment.
+#define NZ_KARG __attribute__((address_space(4)))
+#define NZ_GLOBAL __attribute__((address_space(1)))
+
+template <class A>
+__device__ __forceinline__ const NZ_KARG A &kernel_args()
+{
+    return *(const NZ_KARG A *)__builtin_amdgcn_kernarg_segment_ptr();
+}
+
 // ---------------------------------------------------------------------------
 // Rail / segment geometry, as seen by the kernels
 // ---------------------------------------------------------------------------
@@ -57,7 +70,7 @@ struct SegTile {
     u64 tile_base;      // first vector of the aligned tile the run lies in
 };
 
-__device__ __forceinline__ void decode_block(const RailGeom &g, u32 block, u32 &rail, u32 &idx,
+__device__ __forceinline__ void decode_block(const NZ_KARG RailGeom &g, u32 block, u32 &rail, u32 &idx,
                                              u32 &tile)
 {
     u32 k = 0;
@@ -72,7 +85,7 @@ __device__ __forceinline__ void decode_block(const RailGeom &g, u32 block, u32 &
 // workgroup's accesses are aligned to the tile size wherever the segment
 // boundary is; the first and last tile of a segment are simply shorter.
 template <int TILE_VECS>
-__device__ __forceinline__ SegTile segment_tile(const RailGeom &g, u32 rail, u32 seg, u32 tile,
+__device__ __forceinline__ SegTile segment_tile(const NZ_KARG RailGeom &g, u32 rail, u32 seg, u32 tile,
                                                 u32 elem_shift)
 {
     SegTile t;
@@ -123,6 +136,7 @@ struct TF32 {
     {
         return vec16_of(as_u32(a[0]), as_u32(a[1]), as_u32(a[2]), as_u32(a[3]));
     }
+    static __device__ __forceinline__ acc_t lane(const vec16 &v, int l) { return as_f32(v[l]); }
     static __device__ __forceinline__ acc_t widen1(elem_t e) { return as_f32(e); }
     static __device__ __forceinline__ elem_t narrow1(acc_t a) { return as_u32(a); }
 };
@@ -139,6 +153,7 @@ struct TI32 {
     {
         return vec16_of(a[0], a[1], a[2], a[3]);
     }
+    static __device__ __forceinline__ acc_t lane(const vec16 &v, int l) { return v[l]; }
     static __device__ __forceinline__ acc_t widen1(elem_t e) { return e; }
     static __device__ __forceinline__ elem_t narrow1(acc_t a) { return a; }
 };
@@ -163,6 +178,10 @@ struct TBF16 {
     static __device__ __forceinline__ vec16 narrow(const acc_t (&a)[kLanes])
     {
         return vec16_of(pair(a[0], a[1]), pair(a[2], a[3]), pair(a[4], a[5]), pair(a[6], a[7]));
+    }
+    static __device__ __forceinline__ acc_t lane(const vec16 &v, int l)
+    {
+        return as_f32((l & 1) ? (v[l >> 1] & 0xffff0000u) : (v[l >> 1] << 16));
     }
     static __device__ __forceinline__ acc_t widen1(elem_t e) { return as_f32((u32)e << 16); }
     static __device__ __forceinline__ elem_t narrow1(acc_t a)
@@ -195,6 +214,12 @@ struct TF16 {
     {
         return vec16_of(pair(a[0], a[1]), pair(a[2], a[3]), pair(a[4], a[5]), pair(a[6], a[7]));
     }
+    static __device__ __forceinline__ acc_t lane(const vec16 &v, int l)
+    {
+        const u32 w = v[l >> 1];
+        const unsigned short h = (unsigned short)((l & 1) ? (w >> 16) : (w & 0xffffu));
+        return (float)__builtin_bit_cast(_Float16, h);
+    }
     static __device__ __forceinline__ acc_t widen1(elem_t e)
     {
         return (float)__builtin_bit_cast(_Float16, e);
@@ -216,16 +241,20 @@ struct VecPacket {
     static __device__ __forceinline__ raw_t load(const void *base, u64 byte_off)
     {
         return __builtin_nontemporal_load(
-            reinterpret_cast<const vec16 *>(static_cast<const char *>(base) + byte_off));
+            (const NZ_GLOBAL vec16 *)(static_cast<const char *>(base) + byte_off));
     }
     static __device__ __forceinline__ void store(void *base, u64 byte_off, const raw_t &v)
     {
-        __builtin_nontemporal_store(v,
-                                    reinterpret_cast<vec16 *>(static_cast<char *>(base) + byte_off));
+        __builtin_nontemporal_store(v, (NZ_GLOBAL vec16 *)(static_cast<char *>(base) + byte_off));
     }
     static __device__ __forceinline__ void widen(const raw_t &r, typename T::acc_t (&a)[kLanes])
     {
         T::widen(r, a);
+    }
+    // Lane l (a compile-time constant after unrolling) of the vector, widened.
+    static __device__ __forceinline__ typename T::acc_t lane(const raw_t &r, int l)
+    {
+        return T::lane(r, l);
     }
     static __device__ __forceinline__ raw_t narrow(const typename T::acc_t (&a)[kLanes])
     {
@@ -239,16 +268,17 @@ struct ElemPacket {
     static constexpr int kLanes = 1;
     static __device__ __forceinline__ raw_t load(const void *base, u64 byte_off)
     {
-        return *reinterpret_cast<const raw_t *>(static_cast<const char *>(base) + byte_off);
+        return *(const NZ_GLOBAL raw_t *)(static_cast<const char *>(base) + byte_off);
     }
     static __device__ __forceinline__ void store(void *base, u64 byte_off, const raw_t &v)
     {
-        *reinterpret_cast<raw_t *>(static_cast<char *>(base) + byte_off) = v;
+        *(NZ_GLOBAL raw_t *)(static_cast<char *>(base) + byte_off) = v;
     }
     static __device__ __forceinline__ void widen(const raw_t &r, typename T::acc_t (&a)[1])
     {
         a[0] = T::widen1(r);
     }
+    static __device__ __forceinline__ typename T::acc_t lane(const raw_t &r, int) { return T::widen1(r); }
     static __device__ __forceinline__ raw_t narrow(const typename T::acc_t (&a)[1])
     {
         return T::narrow1(a[0]);
@@ -277,67 +307,74 @@ struct FusedArgs {
 // With N <= 128 no value passes through more than 3 + 3 + 2 roundings, so the
 // fp32 error stays below 8 * 2^-24 * sum|x|, and the eight loads of a block
 // are independent and in flight together.
+// Sum of a full block of eight nodes starting at node m0: a balanced tree.
 template <class T, class P>
-__device__ __forceinline__ void reduce_nodes(const FusedArgs &a, u64 byte_off,
-                                             typename T::acc_t (&res)[P::kLanes])
+__device__ __forceinline__ void block_sum8(const NZ_KARG FusedArgs &a, u32 m0, u64 byte_off,
+                                           typename T::acc_t (&s)[P::kLanes])
+{
+    typename P::raw_t r[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) r[i] = P::load(a.in[m0 + i], byte_off);
+#pragma unroll
+    for (int l = 0; l < P::kLanes; ++l)
+        s[l] = ((P::lane(r[0], l) + P::lane(r[1], l)) + (P::lane(r[2], l) + P::lane(r[3], l))) +
+               ((P::lane(r[4], l) + P::lane(r[5], l)) + (P::lane(r[6], l) + P::lane(r[7], l)));
+}
+
+// Sum of the last, partial block (1 <= nb <= 7 nodes): the same tree with the
+// missing leaves left out.
+template <class T, class P>
+__device__ __forceinline__ void block_sum_tail(const NZ_KARG FusedArgs &a, u32 m0, u32 nb,
+                                               u64 byte_off, typename T::acc_t (&s)[P::kLanes])
+{
+    typedef typename T::acc_t acc_t;
+    typename P::raw_t r[7];
+#pragma unroll
+    for (int i = 0; i < 7; ++i) r[i] = P::load(a.in[(u32)i < nb ? m0 + i : m0], byte_off);
+#pragma unroll
+    for (int l = 0; l < P::kLanes; ++l) {
+        const acc_t p0 = nb > 1 ? P::lane(r[0], l) + P::lane(r[1], l) : P::lane(r[0], l);
+        const acc_t p1 = nb > 3 ? P::lane(r[2], l) + P::lane(r[3], l) : P::lane(r[2], l);
+        const acc_t p2 = nb > 5 ? P::lane(r[4], l) + P::lane(r[5], l) : P::lane(r[4], l);
+        const acc_t p3 = P::lane(r[6], l);
+        const acc_t lo = nb > 2 ? p0 + p1 : p0;
+        const acc_t hi = nb > 6 ? p2 + p3 : p2;
+        s[l] = nb > 4 ? lo + hi : lo;
+    }
+}
+
+template <class T, class P>
+__device__ __forceinline__ void reduce_bcast_at(const NZ_KARG FusedArgs &a, u64 byte_off)
 {
     typedef typename T::acc_t acc_t;
     constexpr int L = P::kLanes;
     const u32 N = a.g.n_nodes;
+    const u32 n_full = N >> 3, n_tail = N & 7u;
     acc_t run[4][L];
-
-    for (u32 base = 0; base < N; base += 32) {
+    for (u32 b = 0; b < n_full; b += 4) {
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const u32 m0 = base + c * 8;
-            if (m0 >= N) break;
-            const u32 nb = (N - m0 < 8u) ? (N - m0) : 8u;
+            if (b + c >= n_full) break;
             acc_t s[L];
-            if (nb == 8) {
-                typename P::raw_t r[8];
+            block_sum8<T, P>(a, (b + c) * 8, byte_off, s);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) r[i] = P::load(a.in[m0 + i], byte_off);
-                acc_t v[8][L];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) P::widen(r[i], v[i]);
-#pragma unroll
-                for (int l = 0; l < L; ++l)
-                    s[l] = ((v[0][l] + v[1][l]) + (v[2][l] + v[3][l])) +
-                           ((v[4][l] + v[5][l]) + (v[6][l] + v[7][l]));
-            } else {
-                // Last, partial block: same tree with the missing leaves left out.
-                typename P::raw_t r[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    if ((u32)i < nb) r[i] = P::load(a.in[m0 + i], byte_off);
-                acc_t v[8][L];
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    if ((u32)i < nb) P::widen(r[i], v[i]);
-#pragma unroll
-                for (int l = 0; l < L; ++l) {
-                    acc_t p[4];
-#pragma unroll
-                    for (int i = 0; i < 4; ++i)
-                        if ((u32)(2 * i) < nb)
-                            p[i] = ((u32)(2 * i + 1) < nb) ? v[2 * i][l] + v[2 * i + 1][l] : v[2 * i][l];
-                    acc_t lo = (nb > 2) ? p[0] + p[1] : p[0];
-                    if (nb > 4) {
-                        acc_t hi = (nb > 6) ? p[2] + p[3] : p[2];
-                        lo = lo + hi;
-                    }
-                    s[l] = lo;
-                }
-            }
-            if (base == 0) {
-#pragma unroll
-                for (int l = 0; l < L; ++l) run[c][l] = s[l];
-            } else {
-#pragma unroll
-                for (int l = 0; l < L; ++l) run[c][l] = run[c][l] + s[l];
-            }
+            for (int l = 0; l < L; ++l) run[c][l] = (b == 0) ? s[l] : run[c][l] + s[l];
         }
     }
+    if (n_tail) {
+        // The partial block is block number n_full: it goes to running sum n_full mod 4.
+        acc_t s[L];
+        block_sum_tail<T, P>(a, n_full * 8, n_tail, byte_off, s);
+        const u32 slot = n_full & 3u;
+        const bool first = n_full < 4;
+#pragma unroll
+        for (int c = 0; c < 4; ++c)
+            if (slot == (u32)c) {
+#pragma unroll
+                for (int l = 0; l < L; ++l) run[c][l] = first ? s[l] : run[c][l] + s[l];
+            }
+    }
+    acc_t res[L];
 #pragma unroll
     for (int l = 0; l < L; ++l) {
         acc_t t = run[0][l];
@@ -349,47 +386,44 @@ __device__ __forceinline__ void reduce_nodes(const FusedArgs &a, u64 byte_off,
         }
         res[l] = t;
     }
-}
-
-template <class T, class P>
-__device__ __forceinline__ void reduce_bcast_at(const FusedArgs &a, u64 byte_off)
-{
-    typename T::acc_t res[P::kLanes];
-    reduce_nodes<T, P>(a, byte_off, res);
     const typename P::raw_t packed = P::narrow(res);
     for (u32 o = 0; o < a.n_out; ++o) P::store(a.out[o], byte_off, packed);
 }
 
-// One workgroup = one aligned tile of ITERS * 256 vectors of one segment.
-template <class T, int ITERS>
-__global__ __launch_bounds__(kThreads) void nz_fused_reduce_bcast(const FusedArgs a)
+// The grid has two kinds of workgroups.  The first g.tile0[n_rails] of them
+// each take one aligned tile of 256 vectors of one segment and handle the
+// vectors that lie wholly inside it.  They are followed by one workgroup per
+// (rail, segment) for the elements that share a 16-byte vector with a
+// neighbouring segment or with the end of the buffer: one thread per element.
+template <class T>
+__global__ __launch_bounds__(kThreads) void nz_fused_reduce_bcast(const FusedArgs)
 {
-    constexpr int TILE = ITERS * kThreads;
-    u32 rail, seg, tile;
-    decode_block(a.g, blockIdx.x, rail, seg, tile);
-    const SegTile t = segment_tile<TILE>(a.g, rail, seg, tile, T::kShift);
-    if (t.vec_lo >= t.vec_hi) return;
-
-    // Vectors that lie wholly inside the segment.
-    const u64 full_lo = (t.b0 + 15) >> 4, full_hi = t.b1 >> 4;
-    const u64 lo = t.vec_lo > full_lo ? t.vec_lo : full_lo;
-    const u64 hi = t.vec_hi < full_hi ? t.vec_hi : full_hi;
-#pragma unroll 1
-    for (int it = 0; it < ITERS; ++it) {
-        const u64 vec = t.tile_base + (u64)it * kThreads + threadIdx.x;
+    const NZ_KARG FusedArgs &a = kernel_args<FusedArgs>();
+    const u32 n_tiles = a.g.tile0[a.g.n_rails];
+    if (blockIdx.x < n_tiles) {
+        u32 rail, seg, tile;
+        decode_block(a.g, blockIdx.x, rail, seg, tile);
+        const SegTile t = segment_tile<kThreads>(a.g, rail, seg, tile, T::kShift);
+        const u64 full_lo = (t.b0 + 15) >> 4, full_hi = t.b1 >> 4;
+        const u64 lo = t.vec_lo > full_lo ? t.vec_lo : full_lo;
+        const u64 hi = t.vec_hi < full_hi ? t.vec_hi : full_hi;
+        const u64 vec = t.tile_base + threadIdx.x;
         if (vec >= lo && vec < hi) reduce_bcast_at<T, VecPacket<T>>(a, vec << 4);
+        return;
     }
-
-    // Elements of the segment that share a vector with a neighbouring segment
-    // (or with the end of the buffer): one thread per element.
+    const u32 e = blockIdx.x - n_tiles;
+    const u32 rail = e / a.g.n_nodes, seg = e - rail * a.g.n_nodes;
+    const SegTile t = segment_tile<kThreads>(a.g, rail, seg, 0, T::kShift);
+    if (t.b0 == t.b1) return;
+    const u64 full_lo = (t.b0 + 15) >> 4, full_hi = t.b1 >> 4;
     const u64 head_end = (full_lo << 4) < t.b1 ? (full_lo << 4) : t.b1;
     u64 tail_beg = full_hi << 4;
     if (tail_beg < head_end) tail_beg = head_end;
-    const u64 eoff = (u64)threadIdx.x << T::kShift;
-    if (t.vec_lo == (t.b0 >> 4) && t.b0 + eoff < head_end)
-        reduce_bcast_at<T, ElemPacket<T>>(a, t.b0 + eoff);
-    if (t.vec_hi == ((t.b1 + 15) >> 4) && tail_beg + eoff < t.b1)
-        reduce_bcast_at<T, ElemPacket<T>>(a, tail_beg + eoff);
+    // threads 0..7 take the head elements, threads 64..71 the tail elements
+    const u32 lane = threadIdx.x & 63u, part = threadIdx.x >> 6;
+    const u64 eoff = (u64)lane << T::kShift;
+    if (part == 0 && t.b0 + eoff < head_end) reduce_bcast_at<T, ElemPacket<T>>(a, t.b0 + eoff);
+    if (part == 1 && tail_beg + eoff < t.b1) reduce_bcast_at<T, ElemPacket<T>>(a, tail_beg + eoff);
 }
 
 // ---------------------------------------------------------------------------
@@ -427,8 +461,9 @@ __device__ __forceinline__ void ring_at(const void *sent, const void *own, void 
 }
 
 template <class T, int ITERS, bool GATHER>
-__global__ __launch_bounds__(kThreads) void nz_ring_step(const RingArgs a)
+__global__ __launch_bounds__(kThreads) void nz_ring_step(const RingArgs)
 {
+    const NZ_KARG RingArgs &a = kernel_args<RingArgs>();
     constexpr int TILE = ITERS * kThreads;
     u32 rail, r, tile;
     decode_block(a.g, blockIdx.x, rail, r, tile);
@@ -488,8 +523,9 @@ struct CopyArgs {
 // Bytes of the run outside whole destination vectors, and destination vectors
 // whose source words are not all inside the run, are copied element by
 // element, so no access ever leaves [off, off + len) of either buffer.
-__global__ __launch_bounds__(kThreads) void nz_segment_copy(const CopyArgs a)
+__global__ __launch_bounds__(kThreads) void nz_segment_copy(const CopyArgs)
 {
+    const NZ_KARG CopyArgs &a = kernel_args<CopyArgs>();
     __shared__ vec16 stage[kThreads + 1];
 
     const u32 node = blockIdx.y;
@@ -679,13 +715,9 @@ bool written_range_overlaps(std::vector<Range> &v)
 }
 
 template <class T>
-nz_status launch_fused(const FusedArgs &a, u32 blocks, hipStream_t st, int iters)
+nz_status launch_fused(const FusedArgs &a, u32 blocks, hipStream_t st)
 {
-    switch (iters) {
-    case 1: hipLaunchKernelGGL((nz_fused_reduce_bcast<T, 1>), dim3(blocks), dim3(kThreads), 0, st, a); break;
-    case 2: hipLaunchKernelGGL((nz_fused_reduce_bcast<T, 2>), dim3(blocks), dim3(kThreads), 0, st, a); break;
-    default: hipLaunchKernelGGL((nz_fused_reduce_bcast<T, 4>), dim3(blocks), dim3(kThreads), 0, st, a); break;
-    }
+    hipLaunchKernelGGL((nz_fused_reduce_bcast<T>), dim3(blocks), dim3(kThreads), 0, st, a);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? NZ_OK : hip_failed(e, "fused reduce launch");
 }
@@ -710,8 +742,6 @@ nz_status launch_ring(RingArgs &a, u32 blocks, hipStream_t st)
     }
     return NZ_OK;
 }
-
-int g_fused_iters = 1;  // 256-vector sub-tiles per workgroup of the fused kernel
 
 nz_status segment_copy(const void *const *src, void *const *dst, u32 n_nodes, const u64 *seg_off,
                        u32 n_rails, u32 rail, const u32 *seg_ids, u32 n_segs, u32 elem_bytes,
@@ -815,9 +845,6 @@ extern "C" {
 
 const char *nz_last_hip_error(void) { return g_hip_error; }
 
-// Tuning hook: 256-vector sub-tiles per workgroup of the fused kernel (1, 2 or 4).
-void nz_set_fused_tile_iters(int iters) { g_fused_iters = (iters == 2 || iters == 4) ? iters : 1; }
-
 nz_status nz_allreduce_sim(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
                            const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype, nz_mode mode,
                            void *const *out_bufs, void *stream)
@@ -871,9 +898,9 @@ nz_status nz_allreduce_sim(const void *const *node_bufs, uint32_t n_nodes, uint6
 
     if (mode == NZ_FUSED) {
         FusedArgs a;
-        const int iters = g_fused_iters;
-        const u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, (u32)iters * kThreads);
+        u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, kThreads);
         if (blocks == 0) return NZ_ERR_UNSUPPORTED;
+        blocks += (u64)n_rails * n_nodes;  // the workgroups for segment edges
         a.elem_shift = shift;
         a.n_out = 0;
         for (u32 i = 0; i < n_nodes; ++i) {
@@ -883,10 +910,10 @@ nz_status nz_allreduce_sim(const void *const *node_bufs, uint32_t n_nodes, uint6
             if (!dup) a.out[a.n_out++] = out_bufs[i];
         }
         switch (dtype) {
-        case NZ_F32: return launch_fused<TF32>(a, (u32)blocks, st, iters);
-        case NZ_I32: return launch_fused<TI32>(a, (u32)blocks, st, iters);
-        case NZ_BF16: return launch_fused<TBF16>(a, (u32)blocks, st, iters);
-        case NZ_F16: return launch_fused<TF16>(a, (u32)blocks, st, iters);
+        case NZ_F32: return launch_fused<TF32>(a, (u32)blocks, st);
+        case NZ_I32: return launch_fused<TI32>(a, (u32)blocks, st);
+        case NZ_BF16: return launch_fused<TBF16>(a, (u32)blocks, st);
+        case NZ_F16: return launch_fused<TF16>(a, (u32)blocks, st);
         }
         return NZ_ERR_INVALID_ARG;
     }

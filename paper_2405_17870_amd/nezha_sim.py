@@ -73,8 +73,6 @@ def load() -> ctypes.CDLL:
     for name in ("nz_rail_partition", "nz_rail_partition_ex", "nz_segment_map",
                  "nz_allreduce_sim", "nz_pack", "nz_unpack"):
         getattr(lib, name).restype = i32
-    lib.nz_set_fused_tile_iters.argtypes = [i32]
-    lib.nz_set_fused_tile_iters.restype = None
     _lib = lib
     return lib
 
@@ -175,8 +173,3 @@ def nz_unpack(send_bufs: Sequence, seg_off: np.ndarray, rail: int, seg_ids: Sequ
     _check(lib.nz_unpack(_ptr_array(send_bufs), n_nodes, seg.ctypes.data, n_rails, rail,
                          _u32_array(seg_ids), len(seg_ids), elem_bytes, _ptr_array(node_bufs),
                          _stream_handle(stream)))
-
-
-def set_fused_tile_iters(iters: int) -> None:
-    """Tuning hook: 256-vector sub-tiles per workgroup of the fused kernel (1, 2 or 4)."""
-    load().nz_set_fused_tile_iters(int(iters))
