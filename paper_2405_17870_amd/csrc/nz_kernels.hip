@@ -70,6 +70,11 @@ struct SegTile {
     u64 tile_base;      // first vector of the aligned tile the run lies in
 };
 
+// Workgroup number -> (rail, index, tile).  With INDEX_FASTEST consecutive
+// workgroups take the same tile number of consecutive indices (nodes), so the
+// workgroups in flight at one time write to many different buffers; otherwise
+// they walk through one index's tiles first.
+template <bool INDEX_FASTEST>
 __device__ __forceinline__ void decode_block(const NZ_KARG RailGeom &g, u32 block, u32 &rail, u32 &idx,
                                              u32 &tile)
 {
@@ -77,8 +82,13 @@ __device__ __forceinline__ void decode_block(const NZ_KARG RailGeom &g, u32 bloc
     while (k + 1 < g.n_rails && block >= g.tile0[k + 1]) ++k;
     const u32 local = block - g.tile0[k];
     rail = k;
-    idx = local / g.tps[k];
-    tile = local - idx * g.tps[k];
+    if (INDEX_FASTEST) {
+        tile = local / g.n_nodes;
+        idx = local - tile * g.n_nodes;
+    } else {
+        idx = local / g.tps[k];
+        tile = local - idx * g.tps[k];
+    }
 }
 
 // Tiles lie on a grid of TILE_VECS vectors that is global to the buffers, so a
@@ -402,7 +412,7 @@ __global__ __launch_bounds__(kThreads) void nz_fused_reduce_bcast(const FusedArg
     const u32 n_tiles = a.g.tile0[a.g.n_rails];
     if (blockIdx.x < n_tiles) {
         u32 rail, seg, tile;
-        decode_block(a.g, blockIdx.x, rail, seg, tile);
+        decode_block<false>(a.g, blockIdx.x, rail, seg, tile);
         const SegTile t = segment_tile<kThreads>(a.g, rail, seg, tile, T::kShift);
         const u64 full_lo = (t.b0 + 15) >> 4, full_hi = t.b1 >> 4;
         const u64 lo = t.vec_lo > full_lo ? t.vec_lo : full_lo;
@@ -466,7 +476,7 @@ __global__ __launch_bounds__(kThreads) void nz_ring_step(const RingArgs)
     const NZ_KARG RingArgs &a = kernel_args<RingArgs>();
     constexpr int TILE = ITERS * kThreads;
     u32 rail, r, tile;
-    decode_block(a.g, blockIdx.x, rail, r, tile);
+    decode_block<false>(a.g, blockIdx.x, rail, r, tile);
     const u32 N = a.g.n_nodes;
     const u32 d = (r + 1 == N) ? 0 : r + 1;
     const u32 seg = GATHER ? (r + 1 + N - a.step) % N : (r + N - a.step) % N;
@@ -500,7 +510,10 @@ __global__ __launch_bounds__(kThreads) void nz_ring_step(const RingArgs)
 // ---------------------------------------------------------------------------
 
 constexpr int kCopyMaxRuns = 40;  // runs per launch; longer lists take several launches
-constexpr int kCopyIters = 4;     // 256-vector sub-tiles per workgroup
+#ifndef NZ_COPY_ITERS
+#define NZ_COPY_ITERS 2
+#endif
+constexpr int kCopyIters = NZ_COPY_ITERS;  // 256-vector sub-tiles per workgroup
 
 // One run: len bytes from src_off in every source buffer to dst_off in the
 // matching destination buffer.  All three are multiples of the element size.
@@ -511,6 +524,7 @@ struct CopyArgs {
     u32 tile0[kCopyMaxRuns + 1];  // first workgroup (per node) of each run
     u32 n_runs;
     u32 elem_bytes;
+    u32 n_nodes;
     const void *src[NZ_MAX_NODES];
     void *dst[NZ_MAX_NODES];
 };
@@ -528,10 +542,13 @@ __global__ __launch_bounds__(kThreads) void nz_segment_copy(const CopyArgs)
     const NZ_KARG CopyArgs &a = kernel_args<CopyArgs>();
     __shared__ vec16 stage[kThreads + 1];
 
-    const u32 node = blockIdx.y;
+    // Node index fastest: the workgroups in flight at one time cover the same
+    // tiles of many nodes' buffers rather than one buffer end to end.
+    const u32 per_node = blockIdx.x / a.n_nodes;
+    const u32 node = blockIdx.x - per_node * a.n_nodes;
     u32 run = 0;
-    while (run + 1 < a.n_runs && blockIdx.x >= a.tile0[run + 1]) ++run;
-    const u32 tile = blockIdx.x - a.tile0[run];
+    while (run + 1 < a.n_runs && per_node >= a.tile0[run + 1]) ++run;
+    const u32 tile = per_node - a.tile0[run];
 
     const char *src = static_cast<const char *>(a.src[node]);
     char *dst = static_cast<char *>(a.dst[node]);
@@ -722,7 +739,10 @@ nz_status launch_fused(const FusedArgs &a, u32 blocks, hipStream_t st)
     return e == hipSuccess ? NZ_OK : hip_failed(e, "fused reduce launch");
 }
 
-constexpr int kRingIters = 4;
+#ifndef NZ_RING_ITERS
+#define NZ_RING_ITERS 2
+#endif
+constexpr int kRingIters = NZ_RING_ITERS;
 
 template <class T>
 nz_status launch_ring(RingArgs &a, u32 blocks, hipStream_t st)
@@ -824,15 +844,16 @@ nz_status segment_copy(const void *const *src, void *const *dst, u32 n_nodes, co
             a.tile0[r] = (u32)blocks;
             const u64 v0 = a.dst_off[r] >> 4, v1 = (a.dst_off[r] + run.len + 15) >> 4;
             blocks += (v1 - 1) / TILE - v0 / TILE + 1;
-            if (blocks > 0x7fffffffull) return NZ_ERR_UNSUPPORTED;
+            if (blocks * n_nodes > 0x7fffffffull) return NZ_ERR_UNSUPPORTED;
         }
         a.tile0[r] = (u32)blocks;
         a.n_runs = r;
+        a.n_nodes = n_nodes;
         for (u32 m = 0; m < n_nodes; ++m) {
             a.src[m] = src[m];
             a.dst[m] = dst[m];
         }
-        hipLaunchKernelGGL(nz_segment_copy, dim3((u32)blocks, n_nodes), dim3(kThreads), 0, st, a);
+        hipLaunchKernelGGL(nz_segment_copy, dim3((u32)(blocks * n_nodes)), dim3(kThreads), 0, st, a);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_failed(e, "segment copy launch");
     }
