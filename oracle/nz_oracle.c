@@ -296,19 +296,14 @@ static void add_into(int dtype, void *dst, const void *src, uint64_t off, uint64
  * stop_after_reduce_scatter != 0 returns after the first N-1 steps.
  * sent_bytes[i] (may be NULL) is incremented by what node i puts on the wire.
  */
-int orc_ring_allreduce(int dtype, void *const *buf, uint32_t n_nodes, uint64_t n,
-                       const uint64_t *seg, uint32_t n_rails,
-                       int stop_after_reduce_scatter, uint64_t *sent_bytes)
+static void ring_reduce_scatter(int dtype, int e, void *const *buf, uint32_t N,
+                                const uint64_t *seg, uint32_t n_rails, uint64_t *sent_bytes)
 {
-    int e = elem_bytes_of(dtype);
-    if (!buf || !seg || n_nodes == 0 || n_rails == 0 || e == 0) return ORC_BAD;
-    (void)n;
-    const uint32_t N = n_nodes;
     for (uint32_t s = 0; s + 1 < N; ++s) {
         for (uint32_t k = 0; k < n_rails; ++k) {
             const uint64_t *row = seg + (size_t)k * (N + 1);
             for (uint32_t r = 0; r < N; ++r) {
-                uint32_t j = (r + N - s % N) % N;
+                uint32_t j = (r + N - s) % N;
                 uint32_t d = (r + 1) % N;
                 uint64_t off = row[j], len = row[j + 1] - row[j];
                 add_into(dtype, buf[d], buf[r], off, len);
@@ -316,12 +311,16 @@ int orc_ring_allreduce(int dtype, void *const *buf, uint32_t n_nodes, uint64_t n
             }
         }
     }
-    if (stop_after_reduce_scatter) return ORC_OK;
+}
+
+static void ring_allgather(int e, void *const *buf, uint32_t N, const uint64_t *seg,
+                           uint32_t n_rails, uint64_t *sent_bytes)
+{
     for (uint32_t s = 0; s + 1 < N; ++s) {
         for (uint32_t k = 0; k < n_rails; ++k) {
             const uint64_t *row = seg + (size_t)k * (N + 1);
             for (uint32_t r = 0; r < N; ++r) {
-                uint32_t j = (r + 1 + N - s % N) % N;
+                uint32_t j = (r + 1 + N - s) % N;
                 uint32_t d = (r + 1) % N;
                 uint64_t off = row[j], len = row[j + 1] - row[j];
                 memcpy((char *)buf[d] + off * e, (const char *)buf[r] + off * e, len * e);
@@ -329,6 +328,34 @@ int orc_ring_allreduce(int dtype, void *const *buf, uint32_t n_nodes, uint64_t n
             }
         }
     }
+}
+
+int orc_ring_allreduce(int dtype, void *const *buf, uint32_t n_nodes, uint64_t n,
+                       const uint64_t *seg, uint32_t n_rails,
+                       int stop_after_reduce_scatter, uint64_t *sent_bytes)
+{
+    int e = elem_bytes_of(dtype);
+    if (!buf || !seg || n_nodes == 0 || n_rails == 0 || e == 0) return ORC_BAD;
+    (void)n;
+    ring_reduce_scatter(dtype, e, buf, n_nodes, seg, n_rails, sent_bytes);
+    if (!stop_after_reduce_scatter)
+        ring_allgather(e, buf, n_nodes, seg, n_rails, sent_bytes);
+    return ORC_OK;
+}
+
+/*
+ * The allgather half on its own: on entry node r's buffer holds valid data in
+ * segment (r + 1) mod N of every rail (what the reduce-scatter leaves it
+ * owning); on exit every buffer holds every segment.  N - 1 steps, node r
+ * sending segment (r + 1 - s) mod N to node (r + 1) mod N in step s.
+ */
+int orc_ring_allgather(int dtype, void *const *buf, uint32_t n_nodes, uint64_t n,
+                       const uint64_t *seg, uint32_t n_rails, uint64_t *sent_bytes)
+{
+    int e = elem_bytes_of(dtype);
+    if (!buf || !seg || n_nodes == 0 || n_rails == 0 || e == 0) return ORC_BAD;
+    (void)n;
+    ring_allgather(e, buf, n_nodes, seg, n_rails, sent_bytes);
     return ORC_OK;
 }
 

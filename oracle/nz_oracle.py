@@ -27,7 +27,7 @@ _NP_STORAGE = {F32: np.float32, BF16: np.uint16, F16: np.uint16, I32: np.int32}
 __all__ = [
     "F32", "BF16", "F16", "I32", "ELEM_BYTES", "build", "threads",
     "rail_partition", "segment_map", "sum_float", "sum_i32", "round_to_storage",
-    "ring_allreduce", "pack", "unpack",
+    "ring_allreduce", "ring_allgather", "pack", "unpack",
     "bf16_to_f32", "f32_to_bf16", "f16_to_f32", "f32_to_f16", "storage_dtype",
 ]
 
@@ -56,6 +56,7 @@ def _L():
         lib.orc_sum_i32.argtypes = [vp, u32, u64, vp]
         lib.orc_round_to_storage.argtypes = [i32, vp, u64, vp]
         lib.orc_ring_allreduce.argtypes = [i32, vp, u32, u64, vp, u32, i32, vp]
+        lib.orc_ring_allgather.argtypes = [i32, vp, u32, u64, vp, u32, vp]
         lib.orc_pack.argtypes = [vp, vp, u32, u32, vp, u32, u32, vp, vp]
         lib.orc_unpack.argtypes = [vp, vp, u32, u32, vp, u32, u32, vp]
         lib.orc_bf16_to_f32.argtypes = [ctypes.c_uint16]
@@ -172,6 +173,21 @@ def ring_allreduce(dtype: int, node_bufs: Sequence[np.ndarray], seg: np.ndarray,
     _check(_L().orc_ring_allreduce(dtype, _ptr_array(bufs), len(bufs), n, seg.ctypes.data, R,
                                    1 if reduce_scatter_only else 0, sent.ctypes.data),
            "ring_allreduce")
+    return bufs, sent
+
+
+def ring_allgather(dtype: int, node_bufs: Sequence[np.ndarray], seg: np.ndarray
+                   ) -> Tuple[List[np.ndarray], np.ndarray]:
+    """The allgather half of the ring on private copies (Eq. 1): node r enters owning segment
+    (r + 1) mod N of every rail.  Returns (per-node result buffers, bytes each node sent)."""
+    bufs = [_as_storage(a, dtype).copy() for a in node_bufs]
+    n = bufs[0].size
+    seg = np.ascontiguousarray(seg, dtype=np.uint64)
+    R, Np1 = seg.shape
+    assert Np1 == len(bufs) + 1
+    sent = np.zeros(len(bufs), dtype=np.uint64)
+    _check(_L().orc_ring_allgather(dtype, _ptr_array(bufs), len(bufs), n, seg.ctypes.data, R,
+                                   sent.ctypes.data), "ring_allgather")
     return bufs, sent
 
 

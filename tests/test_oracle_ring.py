@@ -128,3 +128,42 @@ def test_rails_do_not_interfere(orc):
         ref = out[0] if ref is None else ref
         assert all((o == ref).all() for o in out)
         assert int(sent.sum()) == 2 * (N - 1) * n * 4
+
+
+@pytest.mark.parametrize("N,R", [(1, 1), (2, 1), (3, 2), (8, 2), (13, 3)])
+def test_allgather_alone_spreads_each_owner_segment(orc, N, R):
+    # node r enters owning segment (r+1) mod N of every rail: mark it with the owner's id, fill
+    # the rest with a canary; afterwards every buffer must read owner(x) * 1000 + x mod 1000
+    rnd = random.Random(N + 10 * R)
+    n = rnd.randint(N, 900)
+    seg = orc.segment_map(orc.rail_partition(n, [rnd.randint(1, 9) for _ in range(R)], 4, 16), N)
+    want = np.empty(n, dtype=np.int32)
+    bufs = [np.full(n, -7, dtype=np.int32) for _ in range(N)]
+    for k in range(R):
+        for j in range(N):
+            owner = (j - 1) % N
+            lo, hi = int(seg[k, j]), int(seg[k, j + 1])
+            vals = owner * 1000 + (np.arange(lo, hi) % 1000)
+            bufs[owner][lo:hi] = vals
+            want[lo:hi] = vals
+    orig = [b.copy() for b in bufs]
+    out, sent = orc.ring_allgather(orc.I32, bufs, seg)
+    for o in out:
+        assert (o == want).all()
+    assert int(sent.sum()) == (N - 1) * n * 4                       # half of Eq. 1's volume
+    for b, o in zip(bufs, orig):                                    # the oracle works on private copies
+        assert (b == o).all()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "i32"])
+def test_reduce_scatter_then_allgather_is_the_allreduce(orc, dtype):
+    N, n = 7, 501
+    code = {"f32": orc.F32, "bf16": orc.BF16, "i32": orc.I32}[dtype]
+    bufs = [inputs.to_host_storage(inputs.node_buffer(dtype, n, 31, i, std=1.0)) for i in range(N)]
+    seg = orc.segment_map(orc.rail_partition(n, [5, 2, 1], bufs[0].itemsize, 16), N)
+    full, sent_full = orc.ring_allreduce(code, bufs, seg)
+    rs, sent_rs = orc.ring_allreduce(code, bufs, seg, reduce_scatter_only=True)
+    both, sent_ag = orc.ring_allgather(code, rs, seg)
+    for a, b in zip(full, both):
+        assert np.array_equal(a, b)
+    assert np.array_equal(sent_full, sent_rs + sent_ag)
