@@ -39,7 +39,8 @@ def parse_args():
     p.add_argument("--warmup", type=int, default=2)
     p.add_argument("--workload", default="c4", help="c1, c1_i32, c2, c3, c4 (default), c5")
     p.add_argument("--parts", default="fused,ring,pack,unpack",
-                   help="comma list of parts to run in a step (default: all four)")
+                   help="comma list of parts to run in a step (default: all four); also available: "
+                        "rs, ag = fused reduce-scatter-only / allgather-only")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--placement", default="spread", choices=["spread", "packed", "torch"],
                    help="where the buffers live in HBM: spread = inputs in the first 96 GiB region, "
@@ -174,13 +175,19 @@ def main() -> int:
     ids = list(range(N))
     torch.cuda.synchronize()
 
-    alg_bytes = {"fused": 2 * N * S, "ring": 5 * (N - 1) * S, "pack": 2 * N * S, "unpack": 2 * N * S}
+    alg_bytes = {"fused": 2 * N * S, "ring": 5 * (N - 1) * S, "pack": 2 * N * S, "unpack": 2 * N * S,
+                 # optional parts: the two halves on their own, fused form
+                 "rs": (N + 1) * S, "ag": N * S}
 
     def run_part(p):
         if p == "fused":
             nz.nz_allreduce_sim(ins, n, w.ratios, w.dtype, "fused", outs)
         elif p == "ring":
             nz.nz_allreduce_sim(ins, n, w.ratios, w.dtype, "ring-stepwise", outs)
+        elif p == "rs":
+            nz.nz_reduce_scatter_sim(ins, n, w.ratios, w.dtype, "fused", outs)
+        elif p == "ag":
+            nz.nz_allgather_sim(outs, n, w.ratios, w.dtype, "fused")
         elif p == "pack":
             for k in range(R):
                 nz.nz_pack(ins, seg, k, ids, e, send[k], send[k][0].numel() * e)
@@ -222,11 +229,12 @@ def main() -> int:
                          "algorithmic_bytes": alg_bytes[p]}
 
     head = "fused" if "fused" in parts else parts[0]
-    launches = {"fused": 1, "ring": 2 * (N - 1), "pack": R, "unpack": R}[head]
+    launches = {"fused": 1, "ring": 2 * (N - 1), "pack": R, "unpack": R, "rs": 1, "ag": 1}[head]
     achieved = part_stats[head]["hbm_GBps"]
     roofline = {
         "kernel": {"fused": "nz_fused_reduce_bcast", "ring": "nz_ring_step",
-                   "pack": "nz_segment_copy", "unpack": "nz_segment_copy"}[head],
+                   "pack": "nz_segment_copy", "unpack": "nz_segment_copy",
+                   "rs": "nz_fused_reduce_bcast", "ag": "nz_gather_bcast"}[head],
         "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
         "algorithmic_bytes_per_launch": alg_bytes[head] // launches,

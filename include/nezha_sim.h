@@ -131,6 +131,42 @@ nz_status nz_allreduce_sim(const void *const *node_bufs, uint32_t n_nodes, uint6
                            void *const *out_bufs, void *stream);
 
 /*
+ * The two halves of the allreduce on their own.  (Sec. 2.1.1, Eq. 1: a ring
+ * allreduce is N - 1 reduce-scatter steps followed by N - 1 allgather steps,
+ * each moving M/N per worker; the same section names the phase decomposition
+ * that ZeRO-style training applies to it.)
+ *
+ * nz_reduce_scatter_sim: same arguments as nz_allreduce_sim.  On completion,
+ * for every rail and every segment j, out_bufs[(j - 1) mod N] holds the sum
+ * over all nodes of segment j -- node r owns segment (r + 1) mod N, as after
+ * the reduce-scatter steps of the ring.  The other elements of the output
+ * buffers are unspecified: NZ_FUSED (one launch, each segment read from all
+ * nodes and written to its owner only) leaves them untouched, NZ_RING_STEPWISE
+ * (N - 1 launches) leaves the ring's partial sums in them.  The summation
+ * order, and so every bit of the owned segments, is that of nz_allreduce_sim
+ * in the same mode.  Output buffers must be pairwise distinct; out_bufs[i] may
+ * alias node_bufs[i] only.
+ *
+ * nz_allgather_sim: in place on bufs (host array of n_nodes device pointers,
+ * pairwise distinct, non-overlapping).  On entry node r's buffer holds valid
+ * data in segment (r + 1) mod N of every rail; on exit every buffer holds
+ * every segment.  NZ_RING_STEPWISE: N - 1 launches (step s copies segment
+ * (r + 1 - s) mod N from node r to node r + 1); NZ_FUSED: one launch, each
+ * segment read once from its owner and stored to the other N - 1 buffers.
+ * dtype only fixes the element size.
+ *
+ * nz_reduce_scatter_sim followed by nz_allgather_sim on its outputs gives
+ * bitwise the result of nz_allreduce_sim in the same mode.
+ */
+nz_status nz_reduce_scatter_sim(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
+                                const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype,
+                                nz_mode mode, void *const *out_bufs, void *stream);
+
+nz_status nz_allgather_sim(void *const *bufs, uint32_t n_nodes, uint64_t n_elems,
+                           const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype, nz_mode mode,
+                           void *stream);
+
+/*
  * Pack: stage rail segments into contiguous send buffers.  (Sec. 3.2: data
  * moves from the user's UnboundBuffer into a rail's contiguous Buffer.)
  *

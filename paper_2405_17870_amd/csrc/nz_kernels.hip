@@ -70,11 +70,8 @@ struct SegTile {
     u64 tile_base;      // first vector of the aligned tile the run lies in
 };
 
-// Workgroup number -> (rail, index, tile).  With INDEX_FASTEST consecutive
-// workgroups take the same tile number of consecutive indices (nodes), so the
-// workgroups in flight at one time write to many different buffers; otherwise
-// they walk through one index's tiles first.
-template <bool INDEX_FASTEST>
+// Workgroup number -> (rail, index, tile): a rail's workgroups walk through
+// one index's tiles before the next index.
 __device__ __forceinline__ void decode_block(const NZ_KARG RailGeom &g, u32 block, u32 &rail, u32 &idx,
                                              u32 &tile)
 {
@@ -82,13 +79,8 @@ __device__ __forceinline__ void decode_block(const NZ_KARG RailGeom &g, u32 bloc
     while (k + 1 < g.n_rails && block >= g.tile0[k + 1]) ++k;
     const u32 local = block - g.tile0[k];
     rail = k;
-    if (INDEX_FASTEST) {
-        tile = local / g.n_nodes;
-        idx = local - tile * g.n_nodes;
-    } else {
-        idx = local / g.tps[k];
-        tile = local - idx * g.tps[k];
-    }
+    idx = local / g.tps[k];
+    tile = local - idx * g.tps[k];
 }
 
 // Tiles lie on a grid of TILE_VECS vectors that is global to the buffers, so a
@@ -301,8 +293,8 @@ struct ElemPacket {
 
 struct FusedArgs {
     RailGeom g;
-    u32 n_out;  // distinct output buffers
-    u32 elem_shift;
+    u32 n_out;       // distinct output buffers (broadcast form)
+    u32 owner_only;  // reduce-scatter form: segment j is stored to out[(j - 1) mod N] alone
     const void *in[NZ_MAX_NODES];
     void *out[NZ_MAX_NODES];
 };
@@ -354,7 +346,8 @@ __device__ __forceinline__ void block_sum_tail(const NZ_KARG FusedArgs &a, u32 m
 }
 
 template <class T, class P>
-__device__ __forceinline__ void reduce_bcast_at(const NZ_KARG FusedArgs &a, u64 byte_off)
+__device__ __forceinline__ void reduce_bcast_at(const NZ_KARG FusedArgs &a, u64 byte_off, u32 out_begin,
+                                                u32 out_end)
 {
     typedef typename T::acc_t acc_t;
     constexpr int L = P::kLanes;
@@ -397,7 +390,7 @@ __device__ __forceinline__ void reduce_bcast_at(const NZ_KARG FusedArgs &a, u64 
         res[l] = t;
     }
     const typename P::raw_t packed = P::narrow(res);
-    for (u32 o = 0; o < a.n_out; ++o) P::store(a.out[o], byte_off, packed);
+    for (u32 o = out_begin; o < out_end; ++o) P::store(a.out[o], byte_off, packed);
 }
 
 // The grid has two kinds of workgroups.  The first g.tile0[n_rails] of them
@@ -412,13 +405,15 @@ __global__ __launch_bounds__(kThreads) void nz_fused_reduce_bcast(const FusedArg
     const u32 n_tiles = a.g.tile0[a.g.n_rails];
     if (blockIdx.x < n_tiles) {
         u32 rail, seg, tile;
-        decode_block<false>(a.g, blockIdx.x, rail, seg, tile);
+        decode_block(a.g, blockIdx.x, rail, seg, tile);
         const SegTile t = segment_tile<kThreads>(a.g, rail, seg, tile, T::kShift);
         const u64 full_lo = (t.b0 + 15) >> 4, full_hi = t.b1 >> 4;
         const u64 lo = t.vec_lo > full_lo ? t.vec_lo : full_lo;
         const u64 hi = t.vec_hi < full_hi ? t.vec_hi : full_hi;
         const u64 vec = t.tile_base + threadIdx.x;
-        if (vec >= lo && vec < hi) reduce_bcast_at<T, VecPacket<T>>(a, vec << 4);
+        const u32 owner = (seg == 0 ? a.g.n_nodes : seg) - 1;
+        const u32 o0 = a.owner_only ? owner : 0, o1 = a.owner_only ? owner + 1 : a.n_out;
+        if (vec >= lo && vec < hi) reduce_bcast_at<T, VecPacket<T>>(a, vec << 4, o0, o1);
         return;
     }
     const u32 e = blockIdx.x - n_tiles;
@@ -432,8 +427,10 @@ __global__ __launch_bounds__(kThreads) void nz_fused_reduce_bcast(const FusedArg
     // threads 0..7 take the head elements, threads 64..71 the tail elements
     const u32 lane = threadIdx.x & 63u, part = threadIdx.x >> 6;
     const u64 eoff = (u64)lane << T::kShift;
-    if (part == 0 && t.b0 + eoff < head_end) reduce_bcast_at<T, ElemPacket<T>>(a, t.b0 + eoff);
-    if (part == 1 && tail_beg + eoff < t.b1) reduce_bcast_at<T, ElemPacket<T>>(a, tail_beg + eoff);
+    const u32 owner = (seg == 0 ? a.g.n_nodes : seg) - 1;
+    const u32 o0 = a.owner_only ? owner : 0, o1 = a.owner_only ? owner + 1 : a.n_out;
+    if (part == 0 && t.b0 + eoff < head_end) reduce_bcast_at<T, ElemPacket<T>>(a, t.b0 + eoff, o0, o1);
+    if (part == 1 && tail_beg + eoff < t.b1) reduce_bcast_at<T, ElemPacket<T>>(a, tail_beg + eoff, o0, o1);
 }
 
 // ---------------------------------------------------------------------------
@@ -476,7 +473,7 @@ __global__ __launch_bounds__(kThreads) void nz_ring_step(const RingArgs)
     const NZ_KARG RingArgs &a = kernel_args<RingArgs>();
     constexpr int TILE = ITERS * kThreads;
     u32 rail, r, tile;
-    decode_block<false>(a.g, blockIdx.x, rail, r, tile);
+    decode_block(a.g, blockIdx.x, rail, r, tile);
     const u32 N = a.g.n_nodes;
     const u32 d = (r + 1 == N) ? 0 : r + 1;
     const u32 seg = GATHER ? (r + 1 + N - a.step) % N : (r + N - a.step) % N;
@@ -503,6 +500,46 @@ __global__ __launch_bounds__(kThreads) void nz_ring_step(const RingArgs)
         ring_at<T, ElemPacket<T>, GATHER>(sent, own, dst, t.b0 + eoff);
     if (t.vec_hi == ((t.b1 + 15) >> 4) && tail_beg + eoff < t.b1)
         ring_at<T, ElemPacket<T>, GATHER>(sent, own, dst, tail_beg + eoff);
+}
+
+// Direct allgather: every segment is read once from the node that owns it
+// after a reduce-scatter, node (j - 1) mod N for segment j, and stored to all
+// other nodes' buffers.  Same tiling as a ring step; a pure copy, so T only
+// fixes the element size of the edge path.
+template <class P>
+__device__ __forceinline__ void gather_at(const NZ_KARG RingArgs &a, u32 owner, u64 byte_off)
+{
+    const typename P::raw_t v = P::load(a.out[owner], byte_off);
+    for (u32 m = 0; m < a.g.n_nodes; ++m)
+        if (m != owner) P::store(a.out[m], byte_off, v);
+}
+
+template <class T, int ITERS>
+__global__ __launch_bounds__(kThreads) void nz_gather_bcast(const RingArgs)
+{
+    const NZ_KARG RingArgs &a = kernel_args<RingArgs>();
+    constexpr int TILE = ITERS * kThreads;
+    u32 rail, seg, tile;
+    decode_block(a.g, blockIdx.x, rail, seg, tile);
+    const SegTile t = segment_tile<TILE>(a.g, rail, seg, tile, T::kShift);
+    if (t.vec_lo >= t.vec_hi) return;
+    const u32 owner = (seg == 0 ? a.g.n_nodes : seg) - 1;
+
+    const u64 full_lo = (t.b0 + 15) >> 4, full_hi = t.b1 >> 4;
+    const u64 lo = t.vec_lo > full_lo ? t.vec_lo : full_lo;
+    const u64 hi = t.vec_hi < full_hi ? t.vec_hi : full_hi;
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const u64 vec = t.tile_base + (u64)it * kThreads + threadIdx.x;
+        if (vec >= lo && vec < hi) gather_at<VecPacket<T>>(a, owner, vec << 4);
+    }
+    const u64 head_end = (full_lo << 4) < t.b1 ? (full_lo << 4) : t.b1;
+    u64 tail_beg = full_hi << 4;
+    if (tail_beg < head_end) tail_beg = head_end;
+    const u64 eoff = (u64)threadIdx.x << T::kShift;
+    if (t.vec_lo == (t.b0 >> 4) && t.b0 + eoff < head_end) gather_at<ElemPacket<T>>(a, owner, t.b0 + eoff);
+    if (t.vec_hi == ((t.b1 + 15) >> 4) && tail_beg + eoff < t.b1)
+        gather_at<ElemPacket<T>>(a, owner, tail_beg + eoff);
 }
 
 // ---------------------------------------------------------------------------
@@ -744,23 +781,33 @@ nz_status launch_fused(const FusedArgs &a, u32 blocks, hipStream_t st)
 #endif
 constexpr int kRingIters = NZ_RING_ITERS;
 
+enum Collective { kAllreduce, kReduceScatter, kAllgather };
+
 template <class T>
-nz_status launch_ring(RingArgs &a, u32 blocks, hipStream_t st)
+nz_status launch_ring(RingArgs &a, u32 blocks, hipStream_t st, Collective what)
 {
     const u32 N = a.g.n_nodes;
-    for (u32 s = 0; s + 1 < N; ++s) {
+    for (u32 s = 0; s + 1 < N && what != kAllgather; ++s) {
         a.step = s;
         hipLaunchKernelGGL((nz_ring_step<T, kRingIters, false>), dim3(blocks), dim3(kThreads), 0, st, a);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_failed(e, "ring reduce-scatter launch");
     }
-    for (u32 s = 0; s + 1 < N; ++s) {
+    for (u32 s = 0; s + 1 < N && what != kReduceScatter; ++s) {
         a.step = s;
         hipLaunchKernelGGL((nz_ring_step<T, kRingIters, true>), dim3(blocks), dim3(kThreads), 0, st, a);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_failed(e, "ring allgather launch");
     }
     return NZ_OK;
+}
+
+template <class T>
+nz_status launch_gather(const RingArgs &a, u32 blocks, hipStream_t st)
+{
+    hipLaunchKernelGGL((nz_gather_bcast<T, kRingIters>), dim3(blocks), dim3(kThreads), 0, st, a);
+    const hipError_t e = hipGetLastError();
+    return e == hipSuccess ? NZ_OK : hip_failed(e, "direct allgather launch");
 }
 
 nz_status segment_copy(const void *const *src, void *const *dst, u32 n_nodes, const u64 *seg_off,
@@ -860,15 +907,11 @@ nz_status segment_copy(const void *const *src, void *const *dst, u32 n_nodes, co
     return NZ_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-const char *nz_last_hip_error(void) { return g_hip_error; }
-
-nz_status nz_allreduce_sim(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
-                           const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype, nz_mode mode,
-                           void *const *out_bufs, void *stream)
+// Common host side of the three collectives.  For kAllgather node_bufs and
+// out_bufs are the same array: the operation is in place.
+nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
+                         const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype, nz_mode mode,
+                         void *const *out_bufs, hipStream_t st)
 {
     if (node_bufs == nullptr || out_bufs == nullptr || ratios == nullptr) return NZ_ERR_INVALID_ARG;
     if (n_nodes == 0 || n_rails == 0) return NZ_ERR_INVALID_ARG;
@@ -895,7 +938,7 @@ nz_status nz_allreduce_sim(const void *const *node_bufs, uint32_t n_nodes, uint6
         }
         if (partial_overlap(refs, bytes)) return NZ_ERR_UNSUPPORTED;
     }
-    if (mode == NZ_RING_STEPWISE) {
+    if (mode == NZ_RING_STEPWISE || what != kAllreduce) {
         // Outputs pairwise distinct; an output may alias only its own node's input.
         std::vector<std::pair<uintptr_t, u32>> ins, outs;
         for (u32 i = 0; i < n_nodes; ++i) {
@@ -914,20 +957,33 @@ nz_status nz_allreduce_sim(const void *const *node_bufs, uint32_t n_nodes, uint6
     }
     if (n_elems == 0) return NZ_OK;
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
     const u32 shift = (eb == 4) ? 2 : 1;
+
+    if (mode == NZ_FUSED && what == kAllgather) {
+        RingArgs a;
+        const u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, (u32)kRingIters * kThreads);
+        if (blocks == 0) return NZ_ERR_UNSUPPORTED;
+        a.elem_shift = shift;
+        a.step = 0;
+        for (u32 i = 0; i < n_nodes; ++i) {
+            a.in[i] = out_bufs[i];
+            a.out[i] = out_bufs[i];
+        }
+        if (n_nodes == 1) return NZ_OK;
+        return eb == 4 ? launch_gather<TI32>(a, (u32)blocks, st) : launch_gather<TBF16>(a, (u32)blocks, st);
+    }
 
     if (mode == NZ_FUSED) {
         FusedArgs a;
         u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, kThreads);
         if (blocks == 0) return NZ_ERR_UNSUPPORTED;
         blocks += (u64)n_rails * n_nodes;  // the workgroups for segment edges
-        a.elem_shift = shift;
+        a.owner_only = (what == kReduceScatter) ? 1u : 0u;
         a.n_out = 0;
         for (u32 i = 0; i < n_nodes; ++i) {
             a.in[i] = node_bufs[i];
             bool dup = false;
-            for (u32 o = 0; o < a.n_out; ++o) dup = dup || (a.out[o] == out_bufs[i]);
+            for (u32 o = 0; o < a.n_out && !a.owner_only; ++o) dup = dup || (a.out[o] == out_bufs[i]);
             if (!dup) a.out[a.n_out++] = out_bufs[i];
         }
         switch (dtype) {
@@ -950,19 +1006,49 @@ nz_status nz_allreduce_sim(const void *const *node_bufs, uint32_t n_nodes, uint6
     }
     if (n_nodes == 1) {
         // A ring of one node has no steps: the result is the node's own data.
-        if (out_bufs[0] != node_bufs[0]) {
+        if (what != kAllgather && out_bufs[0] != node_bufs[0]) {
             const hipError_t e = hipMemcpyAsync(out_bufs[0], node_bufs[0], bytes, hipMemcpyDeviceToDevice, st);
             if (e != hipSuccess) return hip_failed(e, "single-node copy");
         }
         return NZ_OK;
     }
     switch (dtype) {
-    case NZ_F32: return launch_ring<TF32>(a, (u32)blocks, st);
-    case NZ_I32: return launch_ring<TI32>(a, (u32)blocks, st);
-    case NZ_BF16: return launch_ring<TBF16>(a, (u32)blocks, st);
-    case NZ_F16: return launch_ring<TF16>(a, (u32)blocks, st);
+    case NZ_F32: return launch_ring<TF32>(a, (u32)blocks, st, what);
+    case NZ_I32: return launch_ring<TI32>(a, (u32)blocks, st, what);
+    case NZ_BF16: return launch_ring<TBF16>(a, (u32)blocks, st, what);
+    case NZ_F16: return launch_ring<TF16>(a, (u32)blocks, st, what);
     }
     return NZ_ERR_INVALID_ARG;
+}
+
+
+}  // namespace
+
+extern "C" {
+
+const char *nz_last_hip_error(void) { return g_hip_error; }
+
+nz_status nz_allreduce_sim(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
+                           const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype, nz_mode mode,
+                           void *const *out_bufs, void *stream)
+{
+    return run_collective(kAllreduce, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype, mode, out_bufs,
+                          static_cast<hipStream_t>(stream));
+}
+
+nz_status nz_reduce_scatter_sim(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
+                                const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype, nz_mode mode,
+                                void *const *out_bufs, void *stream)
+{
+    return run_collective(kReduceScatter, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype, mode,
+                          out_bufs, static_cast<hipStream_t>(stream));
+}
+
+nz_status nz_allgather_sim(void *const *bufs, uint32_t n_nodes, uint64_t n_elems, const uint32_t *ratios,
+                           uint32_t n_rails, nz_dtype dtype, nz_mode mode, void *stream)
+{
+    return run_collective(kAllgather, reinterpret_cast<const void *const *>(bufs), n_nodes, n_elems, ratios,
+                          n_rails, dtype, mode, bufs, static_cast<hipStream_t>(stream));
 }
 
 nz_status nz_pack(const void *const *node_bufs, uint32_t n_nodes, const uint64_t *seg_off,

@@ -31,7 +31,8 @@ ELEM_BYTES = {"f32": 4, "bf16": 2, "f16": 2, "i32": 4}
 
 EXPORTS = [
     "nz_status_str", "nz_last_hip_error", "nz_dtype_bytes", "nz_rail_partition",
-    "nz_rail_partition_ex", "nz_segment_map", "nz_allreduce_sim", "nz_pack", "nz_unpack",
+    "nz_rail_partition_ex", "nz_segment_map", "nz_allreduce_sim", "nz_reduce_scatter_sim",
+    "nz_allgather_sim", "nz_pack", "nz_unpack",
 ]
 
 
@@ -68,10 +69,13 @@ def load() -> ctypes.CDLL:
     lib.nz_rail_partition_ex.argtypes = [u64, u32, u32, vp, u32, vp]
     lib.nz_segment_map.argtypes = [vp, u32, u32, vp]
     lib.nz_allreduce_sim.argtypes = [vp, u32, u64, vp, u32, i32, i32, vp, vp]
+    lib.nz_reduce_scatter_sim.argtypes = [vp, u32, u64, vp, u32, i32, i32, vp, vp]
+    lib.nz_allgather_sim.argtypes = [vp, u32, u64, vp, u32, i32, i32, vp]
     lib.nz_pack.argtypes = [vp, u32, vp, u32, u32, vp, u32, u32, vp, u64, vp, vp]
     lib.nz_unpack.argtypes = [vp, u32, vp, u32, u32, vp, u32, u32, vp, vp]
     for name in ("nz_rail_partition", "nz_rail_partition_ex", "nz_segment_map",
-                 "nz_allreduce_sim", "nz_pack", "nz_unpack"):
+                 "nz_allreduce_sim", "nz_reduce_scatter_sim", "nz_allgather_sim", "nz_pack",
+                 "nz_unpack"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -143,6 +147,28 @@ def nz_allreduce_sim(node_bufs: Sequence, n_elems: int, ratios: Sequence[int], d
     _check(lib.nz_allreduce_sim(_ptr_array(node_bufs), len(node_bufs), n_elems,
                                 _u32_array(ratios), len(ratios), DTYPE_CODE[dtype],
                                 MODE_CODE[mode], _ptr_array(out_bufs), _stream_handle(stream)))
+
+
+def nz_reduce_scatter_sim(node_bufs: Sequence, n_elems: int, ratios: Sequence[int], dtype: str,
+                          mode: str, out_bufs: Sequence, stream=None) -> None:
+    """The reduce-scatter half (Sec. 2.1.1, Eq. 1): out_bufs[(j - 1) mod N] receives the sum of
+    segment j of every rail; the rest of the outputs is unspecified."""
+    lib = load()
+    if len(out_bufs) != len(node_bufs):
+        raise ValueError("out_bufs must have one entry per node")
+    _check(lib.nz_reduce_scatter_sim(_ptr_array(node_bufs), len(node_bufs), n_elems,
+                                     _u32_array(ratios), len(ratios), DTYPE_CODE[dtype],
+                                     MODE_CODE[mode], _ptr_array(out_bufs), _stream_handle(stream)))
+
+
+def nz_allgather_sim(bufs: Sequence, n_elems: int, ratios: Sequence[int], dtype: str, mode: str,
+                     stream=None) -> None:
+    """The allgather half, in place (Sec. 2.1.1, Eq. 1): node r enters owning segment
+    (r + 1) mod N of every rail; every buffer leaves holding every segment."""
+    lib = load()
+    _check(lib.nz_allgather_sim(_ptr_array(bufs), len(bufs), n_elems, _u32_array(ratios),
+                                len(ratios), DTYPE_CODE[dtype], MODE_CODE[mode],
+                                _stream_handle(stream)))
 
 
 def nz_pack(node_bufs: Sequence, seg_off: np.ndarray, rail: int, seg_ids: Sequence[int],
