@@ -359,6 +359,80 @@ int orc_ring_allgather(int dtype, void *const *buf, uint32_t n_nodes, uint64_t n
     return ORC_OK;
 }
 
+/*
+ * Ring allreduce with every segment transfer cut into pieces of at most
+ * chunk_elems elements, sent one after another (the "Ring_Chunked" variant
+ * the evaluation section mentions: large packets are split and their
+ * transmission pipelined).  Within a step, piece c of every (rail, node) is
+ * moved before piece c + 1.  The arithmetic per element is that of the plain
+ * ring.  messages[i] (may be NULL) counts the non-empty pieces node i sends.
+ */
+int orc_ring_allreduce_chunked(int dtype, void *const *buf, uint32_t n_nodes, uint64_t n,
+                               const uint64_t *seg, uint32_t n_rails, uint64_t chunk_elems,
+                               uint64_t *sent_bytes, uint64_t *messages)
+{
+    int e = elem_bytes_of(dtype);
+    if (!buf || !seg || n_nodes == 0 || n_rails == 0 || e == 0 || chunk_elems == 0) return ORC_BAD;
+    (void)n;
+    const uint32_t N = n_nodes;
+    uint64_t longest = 0;
+    for (uint32_t k = 0; k < n_rails; ++k)
+        for (uint32_t j = 0; j < N; ++j) {
+            uint64_t len = seg[(size_t)k * (N + 1) + j + 1] - seg[(size_t)k * (N + 1) + j];
+            if (len > longest) longest = len;
+        }
+    const uint64_t n_chunks = (longest + chunk_elems - 1) / chunk_elems;
+    for (int phase = 0; phase < 2; ++phase) {
+        for (uint32_t s = 0; s + 1 < N; ++s) {
+            for (uint64_t c = 0; c < n_chunks; ++c) {
+                for (uint32_t k = 0; k < n_rails; ++k) {
+                    const uint64_t *row = seg + (size_t)k * (N + 1);
+                    for (uint32_t r = 0; r < N; ++r) {
+                        uint32_t j = phase == 0 ? (r + N - s) % N : (r + 1 + N - s) % N;
+                        uint32_t d = (r + 1) % N;
+                        uint64_t len = row[j + 1] - row[j];
+                        uint64_t lo = c * chunk_elems;
+                        if (lo >= len) continue;
+                        uint64_t piece = len - lo < chunk_elems ? len - lo : chunk_elems;
+                        uint64_t off = row[j] + lo;
+                        if (phase == 0)
+                            add_into(dtype, buf[d], buf[r], off, piece);
+                        else
+                            memcpy((char *)buf[d] + off * e, (const char *)buf[r] + off * e, piece * e);
+                        if (sent_bytes) sent_bytes[r] += piece * (uint64_t)e;
+                        if (messages) messages[r] += 1;
+                    }
+                }
+            }
+        }
+    }
+    return ORC_OK;
+}
+
+/* ---------------------------------------------------------------------- */
+/* Fault tolerance (Sec. 4.4)                                              */
+/* ---------------------------------------------------------------------- */
+
+/*
+ * The member network that takes over a failed rail's (ptr, data_length): the
+ * surviving rail that was allocated the most data (the paper takes the rail
+ * handling more data to be the more performant one); among equals the lowest
+ * index.  alive[k] != 0 marks a surviving rail.  Returns ORC_BAD if none
+ * survives.
+ */
+int orc_failover_target(const uint64_t *b, uint32_t n_rails, const uint8_t *alive, uint32_t *target)
+{
+    if (!b || !alive || !target || n_rails == 0) return ORC_BAD;
+    int found = 0;
+    uint64_t best_len = 0;
+    for (uint32_t k = 0; k < n_rails; ++k) {
+        if (!alive[k]) continue;
+        uint64_t len = b[k + 1] - b[k];
+        if (!found || len > best_len) { found = 1; best_len = len; *target = k; }
+    }
+    return found ? ORC_OK : ORC_BAD;
+}
+
 /* ---------------------------------------------------------------------- */
 /* Pack / unpack (Sec. 3.2: UnboundBuffer <-> per-rail Buffer)             */
 /* ---------------------------------------------------------------------- */

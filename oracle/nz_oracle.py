@@ -27,7 +27,7 @@ _NP_STORAGE = {F32: np.float32, BF16: np.uint16, F16: np.uint16, I32: np.int32}
 __all__ = [
     "F32", "BF16", "F16", "I32", "ELEM_BYTES", "build", "threads",
     "rail_partition", "segment_map", "sum_float", "sum_i32", "round_to_storage",
-    "ring_allreduce", "ring_allgather", "pack", "unpack",
+    "ring_allreduce", "ring_allgather", "ring_allreduce_chunked", "failover_target", "pack", "unpack",
     "bf16_to_f32", "f32_to_bf16", "f16_to_f32", "f32_to_f16", "storage_dtype",
 ]
 
@@ -57,6 +57,8 @@ def _L():
         lib.orc_round_to_storage.argtypes = [i32, vp, u64, vp]
         lib.orc_ring_allreduce.argtypes = [i32, vp, u32, u64, vp, u32, i32, vp]
         lib.orc_ring_allgather.argtypes = [i32, vp, u32, u64, vp, u32, vp]
+        lib.orc_ring_allreduce_chunked.argtypes = [i32, vp, u32, u64, vp, u32, u64, vp, vp]
+        lib.orc_failover_target.argtypes = [vp, u32, vp, vp]
         lib.orc_pack.argtypes = [vp, vp, u32, u32, vp, u32, u32, vp, vp]
         lib.orc_unpack.argtypes = [vp, vp, u32, u32, vp, u32, u32, vp]
         lib.orc_bf16_to_f32.argtypes = [ctypes.c_uint16]
@@ -189,6 +191,35 @@ def ring_allgather(dtype: int, node_bufs: Sequence[np.ndarray], seg: np.ndarray
     _check(_L().orc_ring_allgather(dtype, _ptr_array(bufs), len(bufs), n, seg.ctypes.data, R,
                                    sent.ctypes.data), "ring_allgather")
     return bufs, sent
+
+
+def ring_allreduce_chunked(dtype: int, node_bufs: Sequence[np.ndarray], seg: np.ndarray,
+                           chunk_elems: int) -> Tuple[List[np.ndarray], np.ndarray, np.ndarray]:
+    """Ring allreduce with transfers cut into pieces of at most chunk_elems elements
+    (the Ring_Chunked variant of the evaluation section).  Returns (buffers, bytes sent per
+    node, messages sent per node)."""
+    bufs = [_as_storage(a, dtype).copy() for a in node_bufs]
+    n = bufs[0].size
+    seg = np.ascontiguousarray(seg, dtype=np.uint64)
+    R, Np1 = seg.shape
+    assert Np1 == len(bufs) + 1
+    sent = np.zeros(len(bufs), dtype=np.uint64)
+    msgs = np.zeros(len(bufs), dtype=np.uint64)
+    _check(_L().orc_ring_allreduce_chunked(dtype, _ptr_array(bufs), len(bufs), n, seg.ctypes.data,
+                                           R, chunk_elems, sent.ctypes.data, msgs.ctypes.data),
+           "ring_allreduce_chunked")
+    return bufs, sent, msgs
+
+
+def failover_target(rail_off: Sequence[int], alive: Sequence[bool]) -> int:
+    """The surviving rail that takes over a failed rail's slice (Sec. 4.4)."""
+    b = np.ascontiguousarray(rail_off, dtype=np.uint64)
+    a = np.asarray([1 if x else 0 for x in alive], dtype=np.uint8)
+    assert len(a) == len(b) - 1
+    t = ctypes.c_uint32(0)
+    _check(_L().orc_failover_target(b.ctypes.data, len(a), a.ctypes.data, ctypes.byref(t)),
+           "failover_target")
+    return int(t.value)
 
 
 def pack(node_buf: np.ndarray, seg: np.ndarray, rail: int, seg_ids: Sequence[int],

@@ -167,3 +167,35 @@ def test_reduce_scatter_then_allgather_is_the_allreduce(orc, dtype):
     for a, b in zip(full, both):
         assert np.array_equal(a, b)
     assert np.array_equal(sent_full, sent_rs + sent_ag)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "i32"])
+@pytest.mark.parametrize("chunk", [1, 7, 64, 1000, 10**9])
+def test_chunked_ring_is_the_ring_piece_by_piece(orc, dtype, chunk):
+    # splitting a transfer changes how many messages there are, not what they add up to
+    N, n = 5, 803
+    code = {"f32": orc.F32, "bf16": orc.BF16, "i32": orc.I32}[dtype]
+    bufs = [inputs.to_host_storage(inputs.node_buffer(dtype, n, 17, i, std=1.0)) for i in range(N)]
+    seg = orc.segment_map(orc.rail_partition(n, [3, 1], bufs[0].itemsize, 16), N)
+    plain, sent_plain = orc.ring_allreduce(code, bufs, seg)
+    out, sent, msgs = orc.ring_allreduce_chunked(code, bufs, seg, chunk)
+    for a, b in zip(plain, out):
+        assert np.array_equal(a, b)
+    assert np.array_equal(sent, sent_plain)                          # Eq. 1's volume is unchanged
+    # message count, by hand: in both phases node r sends N-1 of the N segments of every rail
+    # (all but segment r+1 while reducing, all but segment r+2 while gathering)
+    lens = np.diff(seg.astype(np.int64), axis=1)                     # [R, N]
+    pieces = -(-lens // chunk)                                       # ceil; 0 for empty segments
+    for r in range(N):
+        want = int(pieces.sum() - pieces[:, (r + 1) % N].sum() + pieces.sum() - pieces[:, (r + 2) % N].sum())
+        assert int(msgs[r]) == want
+
+
+def test_failover_target_is_the_survivor_with_most_data(orc):
+    b = [0, 100, 400, 400, 900, 1000]                                # lengths 100, 300, 0, 500, 100
+    assert orc.failover_target(b, [True] * 5) == 3
+    assert orc.failover_target(b, [True, True, True, False, True]) == 1      # rail 3 failed
+    assert orc.failover_target(b, [True, False, True, False, True]) == 0     # tie 100/100: lowest index
+    assert orc.failover_target(b, [False, False, True, False, False]) == 2   # even an empty rail survives
+    with pytest.raises(ValueError):
+        orc.failover_target(b, [False] * 5)
