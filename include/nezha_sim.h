@@ -167,6 +167,47 @@ nz_status nz_allgather_sim(void *const *bufs, uint32_t n_nodes, uint64_t n_elems
                            void *stream);
 
 /*
+ * Ring_Chunked allreduce.  (Evaluation, GPT-3 scalability: the Ring_Chunked
+ * algorithm splits large data packets and pipelines their transmission.)
+ *
+ * The ring of NZ_RING_STEPWISE with every segment transfer cut into pieces of
+ * at most chunk_elems elements (> 0): each of the 2 (N - 1) steps is issued as
+ * one launch per piece, piece c of every (rail, node) before piece c + 1.
+ * Every element goes through the same additions in the same order as in
+ * NZ_RING_STEPWISE, so the result is bitwise that mode's; what changes is
+ * the number of launches, ceil(longest segment / chunk_elems) per step.
+ * Arguments, aliasing rules and errors as nz_allreduce_sim in ring mode.
+ */
+nz_status nz_allreduce_sim_chunked(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
+                                   const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype,
+                                   uint64_t chunk_elems, void *const *out_bufs, void *stream);
+
+/*
+ * Fault tolerance.  (Sec. 4.4: when a member network fails, its (ptr,
+ * data_length) is handed to the surviving network that was allocated the most
+ * data, which runs the allreduce of that slice after its current task.)
+ *
+ * nz_failover_target: host only.  alive: host, n_rails flags (non-zero =
+ * surviving).  *target receives the surviving rail with the longest range in
+ * rail_off (lowest index among equals); NZ_ERR_INVALID_ARG if none survives.
+ *
+ * nz_allreduce_sim_failover: nz_allreduce_sim with rail failed_rail (<
+ * n_rails) failing.  The surviving rails' slices are processed first; the
+ * failed rail's slice, still cut into the same N segments, follows on the
+ * same stream as a second pass (one more launch in NZ_FUSED, 2 (N - 1) more
+ * in NZ_RING_STEPWISE).  The result is bitwise that of nz_allreduce_sim.
+ * takeover_rail (host, may be NULL) receives nz_failover_target's choice.
+ * NZ_ERR_INVALID_ARG if failed_rail is the only rail.
+ */
+nz_status nz_failover_target(const uint64_t *rail_off, uint32_t n_rails, const uint8_t *alive,
+                             uint32_t *target);
+
+nz_status nz_allreduce_sim_failover(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
+                                    const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype,
+                                    nz_mode mode, void *const *out_bufs, uint32_t failed_rail,
+                                    uint32_t *takeover_rail, void *stream);
+
+/*
  * Pack: stage rail segments into contiguous send buffers.  (Sec. 3.2: data
  * moves from the user's UnboundBuffer into a rail's contiguous Buffer.)
  *

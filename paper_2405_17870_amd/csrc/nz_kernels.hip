@@ -61,6 +61,7 @@ struct RailGeom {
     u32 tps[NZ_MAX_RAILS];       // workgroups reserved per segment of the rail
     u32 n_rails;
     u32 n_nodes;
+    u64 win_off, win_len;        // the piece of every segment this launch works on (elements)
 };
 
 // Work of one workgroup: a run of 16-byte vectors of one segment.
@@ -92,8 +93,11 @@ __device__ __forceinline__ SegTile segment_tile(const NZ_KARG RailGeom &g, u32 r
 {
     SegTile t;
     const u32 rem = g.rem[rail];
-    const u64 beg = g.off[rail] + seg * g.q[rail] + (seg < rem ? seg : rem);
-    const u64 len = g.q[rail] + (seg < rem ? 1u : 0u);
+    u64 beg = g.off[rail] + seg * g.q[rail] + (seg < rem ? seg : rem);
+    u64 len = g.q[rail] + (seg < rem ? 1u : 0u);
+    const u64 skip = len < g.win_off ? len : g.win_off;
+    beg += skip;
+    len = (len - skip) < g.win_len ? (len - skip) : g.win_len;
     t.b0 = beg << elem_shift;
     t.b1 = (beg + len) << elem_shift;
     const u64 v0 = t.b0 >> 4;
@@ -691,27 +695,39 @@ bool aligned256(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255u) 
 
 // Fill the geometry for tiles of tile_vecs 16-byte vectors.  Returns the
 // number of workgroups, or 0 if it does not fit the grid.
+constexpr u64 kNothingToDo = UINT64_MAX;  // every selected rail is empty
+
 u64 build_geometry(RailGeom &g, const u64 *rail_off, u32 n_rails, u32 n_nodes, u32 elem_shift,
-                   u32 tile_vecs)
+                   u32 tile_vecs, u32 rail_mask = 0xffffffffu, u64 piece_elems = UINT64_MAX)
 {
     std::memset(&g, 0, sizeof g);
     g.n_rails = n_rails;
     g.n_nodes = n_nodes;
+    g.win_off = 0;
+    g.win_len = piece_elems;
     u64 total = 0;
     for (u32 k = 0; k < n_rails; ++k) {
-        const u64 len = rail_off[k + 1] - rail_off[k];
+        // A rail left out of this launch keeps its place but has no elements.
+        const u64 len = (rail_mask >> k & 1u) ? rail_off[k + 1] - rail_off[k] : 0;
         g.off[k] = rail_off[k];
         g.q[k] = len / n_nodes;
         g.rem[k] = (u32)(len % n_nodes);
-        // Exact maximum, over the rail's segments, of the tiles a segment touches.
         u64 most = 0;
-        for (u32 j = 0; j < n_nodes && len > 0; ++j) {
-            const u64 beg = g.off[k] + j * g.q[k] + std::min<u64>(j, g.rem[k]);
-            const u64 sl = g.q[k] + (j < g.rem[k] ? 1 : 0);
-            if (sl == 0) continue;
-            const u64 v0 = (beg << elem_shift) >> 4;
-            const u64 v1 = (((beg + sl) << elem_shift) + 15) >> 4;
-            most = std::max<u64>(most, (v1 - 1) / tile_vecs - v0 / tile_vecs + 1);
+        if (piece_elems != UINT64_MAX && len > 0) {
+            // Pieces start anywhere: bound the tiles a piece can touch.
+            const u64 longest = std::min<u64>(g.q[k] + (g.rem[k] ? 1 : 0), piece_elems);
+            const u64 vecs = ((longest << elem_shift) + 15) / 16 + 1;
+            most = longest ? (vecs + tile_vecs - 1) / tile_vecs + 1 : 0;
+        } else {
+            // Exact maximum, over the rail's segments, of the tiles a segment touches.
+            for (u32 j = 0; j < n_nodes && len > 0; ++j) {
+                const u64 beg = g.off[k] + j * g.q[k] + std::min<u64>(j, g.rem[k]);
+                const u64 sl = g.q[k] + (j < g.rem[k] ? 1 : 0);
+                if (sl == 0) continue;
+                const u64 v0 = (beg << elem_shift) >> 4;
+                const u64 v1 = (((beg + sl) << elem_shift) + 15) >> 4;
+                most = std::max<u64>(most, (v1 - 1) / tile_vecs - v0 / tile_vecs + 1);
+            }
         }
         if (most > 0xffffffffull) return 0;
         g.tps[k] = (u32)most;
@@ -721,7 +737,7 @@ u64 build_geometry(RailGeom &g, const u64 *rail_off, u32 n_rails, u32 n_nodes, u
     }
     g.off[n_rails] = rail_off[n_rails];
     g.tile0[n_rails] = (u32)total;
-    return total;
+    return total == 0 ? kNothingToDo : total;
 }
 
 struct PtrRef {
@@ -783,21 +799,29 @@ constexpr int kRingIters = NZ_RING_ITERS;
 
 enum Collective { kAllreduce, kReduceScatter, kAllgather };
 
+// n_pieces > 1: every step is issued as n_pieces launches, piece c of every
+// segment before piece c + 1 (a.g.win_len elements each).
 template <class T>
-nz_status launch_ring(RingArgs &a, u32 blocks, hipStream_t st, Collective what)
+nz_status launch_ring(RingArgs &a, u32 blocks, hipStream_t st, Collective what, u64 n_pieces)
 {
     const u32 N = a.g.n_nodes;
     for (u32 s = 0; s + 1 < N && what != kAllgather; ++s) {
         a.step = s;
-        hipLaunchKernelGGL((nz_ring_step<T, kRingIters, false>), dim3(blocks), dim3(kThreads), 0, st, a);
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return hip_failed(e, "ring reduce-scatter launch");
+        for (u64 c = 0; c < n_pieces; ++c) {
+            a.g.win_off = c * (n_pieces > 1 ? a.g.win_len : 0);
+            hipLaunchKernelGGL((nz_ring_step<T, kRingIters, false>), dim3(blocks), dim3(kThreads), 0, st, a);
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return hip_failed(e, "ring reduce-scatter launch");
+        }
     }
     for (u32 s = 0; s + 1 < N && what != kReduceScatter; ++s) {
         a.step = s;
-        hipLaunchKernelGGL((nz_ring_step<T, kRingIters, true>), dim3(blocks), dim3(kThreads), 0, st, a);
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return hip_failed(e, "ring allgather launch");
+        for (u64 c = 0; c < n_pieces; ++c) {
+            a.g.win_off = c * (n_pieces > 1 ? a.g.win_len : 0);
+            hipLaunchKernelGGL((nz_ring_step<T, kRingIters, true>), dim3(blocks), dim3(kThreads), 0, st, a);
+            const hipError_t e = hipGetLastError();
+            if (e != hipSuccess) return hip_failed(e, "ring allgather launch");
+        }
     }
     return NZ_OK;
 }
@@ -909,9 +933,12 @@ nz_status segment_copy(const void *const *src, void *const *dst, u32 n_nodes, co
 
 // Common host side of the three collectives.  For kAllgather node_bufs and
 // out_bufs are the same array: the operation is in place.
+// rail_mask selects the rails a call works on (bit k = rail k); piece_elems is
+// the Ring_Chunked piece length (UINT64_MAX: whole segments).
 nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
                          const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype, nz_mode mode,
-                         void *const *out_bufs, hipStream_t st)
+                         void *const *out_bufs, hipStream_t st, u32 rail_mask = 0xffffffffu,
+                         u64 piece_elems = UINT64_MAX)
 {
     if (node_bufs == nullptr || out_bufs == nullptr || ratios == nullptr) return NZ_ERR_INVALID_ARG;
     if (n_nodes == 0 || n_rails == 0) return NZ_ERR_INVALID_ARG;
@@ -961,8 +988,10 @@ nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t
 
     if (mode == NZ_FUSED && what == kAllgather) {
         RingArgs a;
-        const u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, (u32)kRingIters * kThreads);
+        const u64 blocks =
+            build_geometry(a.g, rail_off, n_rails, n_nodes, shift, (u32)kRingIters * kThreads, rail_mask);
         if (blocks == 0) return NZ_ERR_UNSUPPORTED;
+        if (blocks == kNothingToDo) return NZ_OK;
         a.elem_shift = shift;
         a.step = 0;
         for (u32 i = 0; i < n_nodes; ++i) {
@@ -975,8 +1004,9 @@ nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t
 
     if (mode == NZ_FUSED) {
         FusedArgs a;
-        u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, kThreads);
+        u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, kThreads, rail_mask);
         if (blocks == 0) return NZ_ERR_UNSUPPORTED;
+        if (blocks == kNothingToDo) return NZ_OK;
         blocks += (u64)n_rails * n_nodes;  // the workgroups for segment edges
         a.owner_only = (what == kReduceScatter) ? 1u : 0u;
         a.n_out = 0;
@@ -996,8 +1026,18 @@ nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t
     }
 
     RingArgs a;
-    const u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, (u32)kRingIters * kThreads);
+    const u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, (u32)kRingIters * kThreads,
+                                      rail_mask, piece_elems);
     if (blocks == 0) return NZ_ERR_UNSUPPORTED;
+    if (blocks == kNothingToDo) return NZ_OK;
+    u64 n_pieces = 1;
+    if (piece_elems != UINT64_MAX) {
+        u64 longest = 0;
+        for (u32 k = 0; k < n_rails; ++k) longest = std::max<u64>(longest, a.g.q[k] + (a.g.rem[k] ? 1 : 0));
+        n_pieces = std::max<u64>((longest + piece_elems - 1) / piece_elems, 1);
+        if (n_pieces > 1u << 20) return NZ_ERR_UNSUPPORTED;  // more launches than anybody means
+        if (n_pieces == 1) a.g.win_len = UINT64_MAX;
+    }
     a.elem_shift = shift;
     a.step = 0;
     for (u32 i = 0; i < n_nodes; ++i) {
@@ -1013,10 +1053,10 @@ nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t
         return NZ_OK;
     }
     switch (dtype) {
-    case NZ_F32: return launch_ring<TF32>(a, (u32)blocks, st, what);
-    case NZ_I32: return launch_ring<TI32>(a, (u32)blocks, st, what);
-    case NZ_BF16: return launch_ring<TBF16>(a, (u32)blocks, st, what);
-    case NZ_F16: return launch_ring<TF16>(a, (u32)blocks, st, what);
+    case NZ_F32: return launch_ring<TF32>(a, (u32)blocks, st, what, n_pieces);
+    case NZ_I32: return launch_ring<TI32>(a, (u32)blocks, st, what, n_pieces);
+    case NZ_BF16: return launch_ring<TBF16>(a, (u32)blocks, st, what, n_pieces);
+    case NZ_F16: return launch_ring<TF16>(a, (u32)blocks, st, what, n_pieces);
     }
     return NZ_ERR_INVALID_ARG;
 }
@@ -1049,6 +1089,65 @@ nz_status nz_allgather_sim(void *const *bufs, uint32_t n_nodes, uint64_t n_elems
 {
     return run_collective(kAllgather, reinterpret_cast<const void *const *>(bufs), n_nodes, n_elems, ratios,
                           n_rails, dtype, mode, bufs, static_cast<hipStream_t>(stream));
+}
+
+nz_status nz_allreduce_sim_chunked(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
+                                   const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype,
+                                   uint64_t chunk_elems, void *const *out_bufs, void *stream)
+{
+    if (chunk_elems == 0) return NZ_ERR_INVALID_ARG;
+    return run_collective(kAllreduce, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype, NZ_RING_STEPWISE,
+                          out_bufs, static_cast<hipStream_t>(stream), 0xffffffffu,
+                          chunk_elems == UINT64_MAX ? UINT64_MAX - 1 : chunk_elems);
+}
+
+nz_status nz_failover_target(const uint64_t *rail_off, uint32_t n_rails, const uint8_t *alive,
+                             uint32_t *target)
+{
+    if (rail_off == nullptr || alive == nullptr || target == nullptr || n_rails == 0)
+        return NZ_ERR_INVALID_ARG;
+    bool found = false;
+    u64 most = 0;
+    for (u32 k = 0; k < n_rails; ++k) {
+        if (rail_off[k + 1] < rail_off[k]) return NZ_ERR_INVALID_ARG;
+        if (!alive[k]) continue;
+        const u64 len = rail_off[k + 1] - rail_off[k];
+        if (!found || len > most) {
+            found = true;
+            most = len;
+            *target = k;
+        }
+    }
+    return found ? NZ_OK : NZ_ERR_INVALID_ARG;
+}
+
+nz_status nz_allreduce_sim_failover(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
+                                    const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype,
+                                    nz_mode mode, void *const *out_bufs, uint32_t failed_rail,
+                                    uint32_t *takeover_rail, void *stream)
+{
+    if (ratios == nullptr || n_rails == 0 || failed_rail >= n_rails) return NZ_ERR_INVALID_ARG;
+    if (n_rails > NZ_MAX_RAILS) return NZ_ERR_UNSUPPORTED;
+    const u32 eb = nz_dtype_bytes(dtype);
+    if (eb == 0) return NZ_ERR_INVALID_ARG;
+    u64 rail_off[NZ_MAX_RAILS + 1];
+    const nz_status ps = nz::rail_partition(n_elems, eb, NZ_RAIL_ALIGN_BYTES, ratios, n_rails, rail_off);
+    if (ps != NZ_OK) return ps;
+    uint8_t alive[NZ_MAX_RAILS];
+    for (u32 k = 0; k < n_rails; ++k) alive[k] = (k != failed_rail);
+    u32 target = 0;
+    const nz_status ts = nz_failover_target(rail_off, n_rails, alive, &target);
+    if (ts != NZ_OK) return ts;  // no rail survives
+    if (takeover_rail) *takeover_rail = target;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // First the surviving rails' own slices, then -- on the same stream, as the
+    // take-over rail's next task -- the failed rail's slice, still cut as it was.
+    const u32 all = (n_rails >= 32) ? 0xffffffffu : ((1u << n_rails) - 1u);
+    const nz_status first = run_collective(kAllreduce, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype,
+                                           mode, out_bufs, st, all & ~(1u << failed_rail));
+    if (first != NZ_OK) return first;
+    return run_collective(kAllreduce, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype, mode, out_bufs, st,
+                          1u << failed_rail);
 }
 
 nz_status nz_pack(const void *const *node_bufs, uint32_t n_nodes, const uint64_t *seg_off,

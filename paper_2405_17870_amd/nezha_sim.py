@@ -32,7 +32,8 @@ ELEM_BYTES = {"f32": 4, "bf16": 2, "f16": 2, "i32": 4}
 EXPORTS = [
     "nz_status_str", "nz_last_hip_error", "nz_dtype_bytes", "nz_rail_partition",
     "nz_rail_partition_ex", "nz_segment_map", "nz_allreduce_sim", "nz_reduce_scatter_sim",
-    "nz_allgather_sim", "nz_pack", "nz_unpack",
+    "nz_allgather_sim", "nz_allreduce_sim_chunked", "nz_failover_target",
+    "nz_allreduce_sim_failover", "nz_pack", "nz_unpack",
 ]
 
 
@@ -71,11 +72,15 @@ def load() -> ctypes.CDLL:
     lib.nz_allreduce_sim.argtypes = [vp, u32, u64, vp, u32, i32, i32, vp, vp]
     lib.nz_reduce_scatter_sim.argtypes = [vp, u32, u64, vp, u32, i32, i32, vp, vp]
     lib.nz_allgather_sim.argtypes = [vp, u32, u64, vp, u32, i32, i32, vp]
+    lib.nz_allreduce_sim_chunked.argtypes = [vp, u32, u64, vp, u32, i32, u64, vp, vp]
+    lib.nz_failover_target.argtypes = [vp, u32, vp, vp]
+    lib.nz_allreduce_sim_failover.argtypes = [vp, u32, u64, vp, u32, i32, i32, vp, u32, vp, vp]
     lib.nz_pack.argtypes = [vp, u32, vp, u32, u32, vp, u32, u32, vp, u64, vp, vp]
     lib.nz_unpack.argtypes = [vp, u32, vp, u32, u32, vp, u32, u32, vp, vp]
     for name in ("nz_rail_partition", "nz_rail_partition_ex", "nz_segment_map",
                  "nz_allreduce_sim", "nz_reduce_scatter_sim", "nz_allgather_sim", "nz_pack",
-                 "nz_unpack"):
+                 "nz_unpack", "nz_allreduce_sim_chunked", "nz_failover_target",
+                 "nz_allreduce_sim_failover"):
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -169,6 +174,45 @@ def nz_allgather_sim(bufs: Sequence, n_elems: int, ratios: Sequence[int], dtype:
     _check(lib.nz_allgather_sim(_ptr_array(bufs), len(bufs), n_elems, _u32_array(ratios),
                                 len(ratios), DTYPE_CODE[dtype], MODE_CODE[mode],
                                 _stream_handle(stream)))
+
+
+def nz_allreduce_sim_chunked(node_bufs: Sequence, n_elems: int, ratios: Sequence[int], dtype: str,
+                             chunk_elems: int, out_bufs: Sequence, stream=None) -> None:
+    """Ring_Chunked allreduce (evaluation section: packets split and pipelined): the ring with
+    every transfer cut into pieces of at most ``chunk_elems`` elements, one launch per piece."""
+    lib = load()
+    if len(out_bufs) != len(node_bufs):
+        raise ValueError("out_bufs must have one entry per node")
+    _check(lib.nz_allreduce_sim_chunked(_ptr_array(node_bufs), len(node_bufs), n_elems,
+                                        _u32_array(ratios), len(ratios), DTYPE_CODE[dtype],
+                                        chunk_elems, _ptr_array(out_bufs), _stream_handle(stream)))
+
+
+def nz_failover_target(rail_off: Sequence[int], alive: Sequence[bool]) -> int:
+    """The surviving rail that takes over a failed rail's slice (Sec. 4.4). Host only."""
+    lib = load()
+    b = np.ascontiguousarray(rail_off, dtype=np.uint64)
+    a = np.asarray([1 if x else 0 for x in alive], dtype=np.uint8)
+    if len(a) != len(b) - 1:
+        raise ValueError("one flag per rail")
+    t = ctypes.c_uint32(0)
+    _check(lib.nz_failover_target(b.ctypes.data, len(a), a.ctypes.data, ctypes.byref(t)))
+    return int(t.value)
+
+
+def nz_allreduce_sim_failover(node_bufs: Sequence, n_elems: int, ratios: Sequence[int], dtype: str,
+                              mode: str, out_bufs: Sequence, failed_rail: int, stream=None) -> int:
+    """Allreduce with one rail failing (Sec. 4.4): its slice is processed as a second pass by
+    the surviving rail with the most data.  Returns that rail's index."""
+    lib = load()
+    if len(out_bufs) != len(node_bufs):
+        raise ValueError("out_bufs must have one entry per node")
+    t = ctypes.c_uint32(0)
+    _check(lib.nz_allreduce_sim_failover(_ptr_array(node_bufs), len(node_bufs), n_elems,
+                                         _u32_array(ratios), len(ratios), DTYPE_CODE[dtype],
+                                         MODE_CODE[mode], _ptr_array(out_bufs), failed_rail,
+                                         ctypes.byref(t), _stream_handle(stream)))
+    return int(t.value)
 
 
 def nz_pack(node_bufs: Sequence, seg_off: np.ndarray, rail: int, seg_ids: Sequence[int],

@@ -72,3 +72,18 @@ def test_host_entry_points_reject_bad_arguments():
     lib = nz.load()
     assert lib.nz_rail_partition(10, 4, None, 1, None) == 1
     assert lib.nz_segment_map(None, 1, 1, None) == 1
+
+
+def test_failover_target_matches_oracle(orc):
+    rnd = random.Random(8)
+    for _ in range(300):
+        R = rnd.randint(1, 8)
+        b = sorted(rnd.randint(0, 1000) for _ in range(R + 1))
+        if rnd.random() < 0.3:                     # force ties
+            b = [0] + [100 * (k + 1) for k in range(R)]
+        alive = [rnd.random() < 0.7 for _ in range(R)]
+        if not any(alive):
+            with pytest.raises(nz.NezhaSimError):
+                nz.nz_failover_target(b, alive)
+            continue
+        assert nz.nz_failover_target(b, alive) == orc.failover_target(b, alive)
