@@ -478,6 +478,106 @@ int orc_unpack(const void *send_buf, const uint64_t *seg, uint32_t n_nodes,
     return ORC_OK;
 }
 
+/* ---------------------------------------------------------------------- */
+/* Data allocation scheme (Sec. 4.3, Eq. 4-8)                              */
+/* ---------------------------------------------------------------------- */
+
+/*
+ * Rail i is modelled by its startup latency t_setup[i] (seconds) and its
+ * effective bandwidth bw[i] (bytes per second); S is the message size.
+ *
+ * Eq. 4: cold start, all data on the best single rail.
+ */
+double orc_t_cold(uint32_t n_rails, const double *t_setup, const double *bw, double S,
+                  uint32_t *best)
+{
+    double t = 0.0;
+    for (uint32_t i = 0; i < n_rails; ++i) {
+        double ti = t_setup[i] + S / bw[i];
+        if (i == 0 || ti < t) { t = ti; if (best) *best = i; }
+    }
+    return t;
+}
+
+/*
+ * Eq. 5: hot start, rail i carries the share alpha[i]; the allreduce ends
+ * when the slowest rail ends.  A rail that is given nothing (alpha = 0) does
+ * not take part, so its startup latency does not count.
+ */
+double orc_t_hot(uint32_t n_rails, const double *t_setup, const double *bw, double S,
+                 const double *alpha, uint32_t *slowest)
+{
+    double t = 0.0;
+    int any = 0;
+    for (uint32_t i = 0; i < n_rails; ++i) {
+        if (!(alpha[i] > 0.0)) continue;
+        double ti = t_setup[i] + alpha[i] * S / bw[i];
+        if (!any || ti > t) { t = ti; any = 1; if (slowest) *slowest = i; }
+    }
+    return t;
+}
+
+/* Euclidean projection of v onto {a : a_i >= 0, sum a_i = 1} (n <= 64). */
+static void project_to_simplex(uint32_t n, double *v)
+{
+    double u[64];
+    for (uint32_t i = 0; i < n; ++i) u[i] = v[i];
+    for (uint32_t i = 1; i < n; ++i) {              /* insertion sort, descending */
+        double x = u[i]; uint32_t j = i;
+        while (j > 0 && u[j - 1] < x) { u[j] = u[j - 1]; --j; }
+        u[j] = x;
+    }
+    double css = 0.0, theta = 0.0;
+    for (uint32_t i = 0; i < n; ++i) {
+        css += u[i];
+        double t = (css - 1.0) / (double)(i + 1);
+        if (u[i] - t > 0.0) theta = t;
+    }
+    for (uint32_t i = 0; i < n; ++i) v[i] = v[i] - theta > 0.0 ? v[i] - theta : 0.0;
+}
+
+/*
+ * The Load Balancer's iteration.
+ *   Eq. 8: starting shares from the rails' latencies T_i under a uniform
+ *          allocation, alpha_i = (T - T_i) / (T (R - 1)) with T = sum T_i and
+ *          R the number of member networks (with that reading the shares sum
+ *          to one).
+ *   Eq. 7: alpha <- alpha - eta * dT_hot/dalpha.  T_hot is a maximum, so the
+ *          derivative is S / bw on the slowest rail and zero elsewhere; after
+ *          the step the shares are projected back onto sum = 1, alpha >= 0.
+ *          The step length falls as eta0 / sqrt(k + 1) and the best iterate is
+ *          kept, as any subgradient iteration must to settle.
+ * Returns the best T_hot found; alpha receives its shares.
+ */
+double orc_balance_iterate(uint32_t n_rails, const double *t_setup, const double *bw, double S,
+                           uint32_t iterations, double *alpha)
+{
+    if (n_rails == 0 || n_rails > 64) return -1.0;
+    double a[64], best_a[64];
+    const uint32_t R = n_rails;
+    if (R == 1) { alpha[0] = 1.0; return t_setup[0] + S / bw[0]; }
+    double T = 0.0, Ti[64], cmax = 0.0;
+    for (uint32_t i = 0; i < R; ++i) {
+        Ti[i] = t_setup[i] + (S / R) / bw[i];
+        T += Ti[i];
+        if (S / bw[i] > cmax) cmax = S / bw[i];
+    }
+    for (uint32_t i = 0; i < R; ++i) a[i] = (T - Ti[i]) / (T * (double)(R - 1));
+    double best_t = orc_t_hot(R, t_setup, bw, S, a, NULL);
+    for (uint32_t i = 0; i < R; ++i) best_a[i] = a[i];
+    const double eta0 = 0.25 / (cmax > 0.0 ? cmax : 1.0);
+    for (uint32_t k = 0; k < iterations; ++k) {
+        uint32_t worst = 0;
+        (void)orc_t_hot(R, t_setup, bw, S, a, &worst);
+        a[worst] -= eta0 / sqrt((double)k + 1.0) * (S / bw[worst]);
+        project_to_simplex(R, a);
+        double t = orc_t_hot(R, t_setup, bw, S, a, NULL);
+        if (t < best_t) { best_t = t; for (uint32_t i = 0; i < R; ++i) best_a[i] = a[i]; }
+    }
+    for (uint32_t i = 0; i < R; ++i) alpha[i] = best_a[i];
+    return best_t;
+}
+
 #ifdef _OPENMP
 #include <omp.h>
 int orc_threads(void) { return omp_get_max_threads(); }

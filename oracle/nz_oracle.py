@@ -28,6 +28,7 @@ __all__ = [
     "F32", "BF16", "F16", "I32", "ELEM_BYTES", "build", "threads",
     "rail_partition", "segment_map", "sum_float", "sum_i32", "round_to_storage",
     "ring_allreduce", "ring_allgather", "ring_allreduce_chunked", "failover_target", "pack", "unpack",
+    "t_cold", "t_hot", "balance_iterate",
     "bf16_to_f32", "f32_to_bf16", "f16_to_f32", "f32_to_f16", "storage_dtype",
 ]
 
@@ -59,6 +60,13 @@ def _L():
         lib.orc_ring_allgather.argtypes = [i32, vp, u32, u64, vp, u32, vp]
         lib.orc_ring_allreduce_chunked.argtypes = [i32, vp, u32, u64, vp, u32, u64, vp, vp]
         lib.orc_failover_target.argtypes = [vp, u32, vp, vp]
+        dbl = ctypes.c_double
+        lib.orc_t_cold.argtypes = [u32, vp, vp, dbl, vp]
+        lib.orc_t_cold.restype = dbl
+        lib.orc_t_hot.argtypes = [u32, vp, vp, dbl, vp, vp]
+        lib.orc_t_hot.restype = dbl
+        lib.orc_balance_iterate.argtypes = [u32, vp, vp, dbl, u32, vp]
+        lib.orc_balance_iterate.restype = dbl
         lib.orc_pack.argtypes = [vp, vp, u32, u32, vp, u32, u32, vp, vp]
         lib.orc_unpack.argtypes = [vp, vp, u32, u32, vp, u32, u32, vp]
         lib.orc_bf16_to_f32.argtypes = [ctypes.c_uint16]
@@ -220,6 +228,39 @@ def failover_target(rail_off: Sequence[int], alive: Sequence[bool]) -> int:
     _check(_L().orc_failover_target(b.ctypes.data, len(a), a.ctypes.data, ctypes.byref(t)),
            "failover_target")
     return int(t.value)
+
+
+def _model(t_setup, bw):
+    ts = np.ascontiguousarray(t_setup, dtype=np.float64)
+    b = np.ascontiguousarray(bw, dtype=np.float64)
+    assert ts.shape == b.shape and ts.ndim == 1
+    return ts, b
+
+
+def t_cold(t_setup, bw, S: float) -> Tuple[float, int]:
+    """Eq. 4: latency with all data on the best single rail; returns (T_cold, that rail)."""
+    ts, b = _model(t_setup, bw)
+    best = ctypes.c_uint32(0)
+    t = _L().orc_t_cold(len(ts), ts.ctypes.data, b.ctypes.data, float(S), ctypes.byref(best))
+    return float(t), int(best.value)
+
+
+def t_hot(t_setup, bw, S: float, alpha) -> float:
+    """Eq. 5: latency when rail i carries the share alpha[i] (rails given nothing sit out)."""
+    ts, b = _model(t_setup, bw)
+    a = np.ascontiguousarray(alpha, dtype=np.float64)
+    return float(_L().orc_t_hot(len(ts), ts.ctypes.data, b.ctypes.data, float(S), a.ctypes.data, None))
+
+
+def balance_iterate(t_setup, bw, S: float, iterations: int = 20000) -> Tuple[np.ndarray, float]:
+    """Eq. 8 starting shares, then Eq. 7's descent; returns (shares, T_hot reached)."""
+    ts, b = _model(t_setup, bw)
+    a = np.zeros(len(ts), dtype=np.float64)
+    t = _L().orc_balance_iterate(len(ts), ts.ctypes.data, b.ctypes.data, float(S), iterations,
+                                 a.ctypes.data)
+    if t < 0:
+        raise ValueError("oracle: balance_iterate: invalid argument")
+    return a, float(t)
 
 
 def pack(node_buf: np.ndarray, seg: np.ndarray, rail: int, seg_ids: Sequence[int],

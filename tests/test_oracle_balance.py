@@ -1,0 +1,81 @@
+"""Pins for the oracle's data-allocation arithmetic (Nezha Sec. 4.3, Eq. 4-8), CPU only.
+
+Pinned by hand-worked two-rail cases, by brute force over a fine grid of the simplex, by the
+special cases the paper states (homogeneous rails share equally; small messages go to the best
+single rail) and by the equal-finish-time property of the optimum."""
+import itertools
+
+import numpy as np
+import pytest
+
+
+def test_eq4_and_eq5_by_hand(orc):
+    ts, bw = [1e-3, 4e-3], [1e9, 4e9]
+    # 8 MB: rail 0 -> 1 ms + 8 ms = 9 ms, rail 1 -> 4 ms + 2 ms = 6 ms
+    t, best = orc.t_cold(ts, bw, 8e6)
+    assert best == 1 and t == pytest.approx(6e-3, rel=1e-12)
+    # 1 MB: 2 ms vs 4.25 ms
+    t, best = orc.t_cold(ts, bw, 1e6)
+    assert best == 0 and t == pytest.approx(2e-3, rel=1e-12)
+    # Eq. 5 with shares 1/4, 3/4 of 8 MB: max(1 + 2, 4 + 1.5) ms
+    assert orc.t_hot(ts, bw, 8e6, [0.25, 0.75]) == pytest.approx(5.5e-3, rel=1e-12)
+    # a rail given nothing sits out: all on rail 0
+    assert orc.t_hot(ts, bw, 8e6, [1.0, 0.0]) == pytest.approx(9e-3, rel=1e-12)
+    # the optimum equalises: 1 + 8a = 4 + 2(1-a) -> a = 0.5, T = 5 ms
+    assert orc.t_hot(ts, bw, 8e6, [0.5, 0.5]) == pytest.approx(5e-3, rel=1e-12)
+
+
+def _grid_best(orc, ts, bw, S, steps):
+    R = len(ts)
+    best = (np.inf, None)
+    for c in itertools.product(range(steps + 1), repeat=R - 1):
+        if sum(c) > steps:
+            continue
+        a = [x / steps for x in c] + [1 - sum(c) / steps]
+        t = orc.t_hot(ts, bw, S, a)
+        if t < best[0]:
+            best = (t, a)
+    return best
+
+
+@pytest.mark.parametrize("ts,bw,S", [
+    ([1e-3, 4e-3], [1e9, 4e9], 8e6),
+    ([1e-3, 4e-3], [1e9, 4e9], 1e6),            # small: everything on rail 0
+    ([9e-6, 982e-6], [0.35e9, 0.2e9], 64e6),    # an RDMA-like and a TCP-like rail
+    ([1e-4, 1e-4, 1e-4], [1e9, 1e9, 1e9], 3e6),
+    ([1e-4, 2e-4, 5e-3], [1e9, 3e9, 2e9], 2e6),
+])
+def test_iteration_reaches_the_brute_force_optimum(orc, ts, bw, S):
+    a, t = orc.balance_iterate(ts, bw, S, 40000)
+    assert a.sum() == pytest.approx(1.0, abs=1e-9) and (a >= 0).all()
+    assert orc.t_hot(ts, bw, S, a) == pytest.approx(t, rel=1e-12)
+    steps = 2000 if len(ts) == 2 else 120
+    tg, ag = _grid_best(orc, ts, bw, S, steps)
+    assert t <= tg * (1 + 1e-9) + 0 or t == pytest.approx(tg, rel=5e-3)
+    assert t == pytest.approx(tg, rel=2e-2)            # the grid itself is coarse for three rails
+    tc, _ = orc.t_cold(ts, bw, S)
+    assert t <= tc * (1 + 1e-12)                        # never worse than the best single rail
+
+
+def test_homogeneous_rails_share_equally_and_bandwidth_proportional(orc):
+    a, _ = orc.balance_iterate([2e-4] * 4, [1e9] * 4, 16e6)
+    assert np.allclose(a, 0.25, atol=2e-3)
+    # equal startup, different bandwidth: shares proportional to bandwidth once setup is negligible
+    a, _ = orc.balance_iterate([1e-6] * 3, [1e9, 2e9, 5e9], 1e9, 40000)
+    assert np.allclose(a, np.array([1, 2, 5]) / 8, atol=3e-3)
+
+
+def test_small_message_goes_to_one_rail(orc):
+    # below (Ts_2 - Ts_1) * B_1 = 3 ms * 1 GB/s = 3 MB the second rail cannot help
+    a, t = orc.balance_iterate([1e-3, 4e-3], [1e9, 4e9], 1e6, 40000)
+    assert a[0] == pytest.approx(1.0, abs=1e-6) and a[1] == pytest.approx(0.0, abs=1e-6)
+    assert t == pytest.approx(orc.t_cold([1e-3, 4e-3], [1e9, 4e9], 1e6)[0], rel=1e-9)
+
+
+def test_eq8_starting_shares_sum_to_one(orc):
+    # zero iterations returns Eq. 8's shares: (T - T_i) / (T (R - 1))
+    ts, bw, S = [1e-3, 2e-3, 3e-3], [1e9, 1e9, 1e9], 3e6
+    a, _ = orc.balance_iterate(ts, bw, S, 0)
+    Ti = np.array([2e-3, 3e-3, 4e-3])
+    assert np.allclose(a, (Ti.sum() - Ti) / (Ti.sum() * 2), rtol=1e-12)
+    assert a.sum() == pytest.approx(1.0, abs=1e-12)
