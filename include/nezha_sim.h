@@ -208,6 +208,43 @@ nz_status nz_allreduce_sim_failover(const void *const *node_bufs, uint32_t n_nod
                                     uint32_t *takeover_rail, void *stream);
 
 /*
+ * Data allocation scheme: how to share a message among rails.  (Sec. 4.3.
+ * Eq. 4: cold start, all data over the best single rail,
+ * T_cold = min_i (T_setup_i + S / B_i).  Eq. 5: hot start with shares alpha
+ * summing to one, T_hot = max_i (T_setup_i + alpha_i S / B_i).  Eq. 6: the
+ * threshold size at which the two are equal.  Eq. 7, 8: the shares are found
+ * by descent on T_hot from latency-derived starting shares.)
+ *
+ * Host only.  rails: host, n_rails models (startup latency in seconds >= 0,
+ * effective bandwidth in bytes per second > 0).  A rail that is given nothing
+ * does not take part in Eq. 5.  nz_balance returns the minimiser of Eq. 5
+ * directly (the point Eq. 7's descent converges to): the rails that take part
+ * all finish at the same time and a rail whose startup latency alone exceeds
+ * that time sits out.  If sharing does not beat the best single rail the
+ * state is cold and that rail gets everything.
+ *   alpha      (host, n_rails doubles, may be NULL): the shares, sum 1;
+ *   ratios     (host, n_rails, may be NULL): the shares as integer weights
+ *              summing to NZ_RATIO_SCALE, ready for nz_rail_partition;
+ *   t_cold, t_hot (may be NULL): Eq. 4 and Eq. 5 for the returned shares;
+ *   best_rail  (may be NULL): the rail of Eq. 4;
+ *   hot        (may be NULL): 1 in the hot-start state, 0 in cold start.
+ * nz_balance_threshold: the message size (bytes) up to which the state is
+ * cold (infinity for a single rail).
+ */
+#define NZ_RATIO_SCALE (1u << 20)
+
+typedef struct {
+    double setup_s;     /* T_setup: startup latency, seconds */
+    double bytes_per_s; /* B: effective bandwidth            */
+} nz_rail_model;
+
+nz_status nz_balance(const nz_rail_model *rails, uint32_t n_rails, double msg_bytes, double *alpha,
+                     uint32_t *ratios, double *t_cold, double *t_hot, uint32_t *best_rail, int *hot);
+
+nz_status nz_balance_threshold(const nz_rail_model *rails, uint32_t n_rails,
+                               double *threshold_bytes);
+
+/*
  * Pack: stage rail segments into contiguous send buffers.  (Sec. 3.2: data
  * moves from the user's UnboundBuffer into a rail's contiguous Buffer.)
  *

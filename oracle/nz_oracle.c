@@ -517,25 +517,6 @@ double orc_t_hot(uint32_t n_rails, const double *t_setup, const double *bw, doub
     return t;
 }
 
-/* Euclidean projection of v onto {a : a_i >= 0, sum a_i = 1} (n <= 64). */
-static void project_to_simplex(uint32_t n, double *v)
-{
-    double u[64];
-    for (uint32_t i = 0; i < n; ++i) u[i] = v[i];
-    for (uint32_t i = 1; i < n; ++i) {              /* insertion sort, descending */
-        double x = u[i]; uint32_t j = i;
-        while (j > 0 && u[j - 1] < x) { u[j] = u[j - 1]; --j; }
-        u[j] = x;
-    }
-    double css = 0.0, theta = 0.0;
-    for (uint32_t i = 0; i < n; ++i) {
-        css += u[i];
-        double t = (css - 1.0) / (double)(i + 1);
-        if (u[i] - t > 0.0) theta = t;
-    }
-    for (uint32_t i = 0; i < n; ++i) v[i] = v[i] - theta > 0.0 ? v[i] - theta : 0.0;
-}
-
 /*
  * The Load Balancer's iteration.
  *   Eq. 8: starting shares from the rails' latencies T_i under a uniform
@@ -543,10 +524,16 @@ static void project_to_simplex(uint32_t n, double *v)
  *          R the number of member networks (with that reading the shares sum
  *          to one).
  *   Eq. 7: alpha <- alpha - eta * dT_hot/dalpha.  T_hot is a maximum, so the
- *          derivative is S / bw on the slowest rail and zero elsewhere; after
- *          the step the shares are projected back onto sum = 1, alpha >= 0.
- *          The step length falls as eta0 / sqrt(k + 1) and the best iterate is
- *          kept, as any subgradient iteration must to settle.
+ *          derivative is S / bw on the slowest rail and zero elsewhere: the
+ *          step takes share away from the slowest rail.  eta is taken relative
+ *          to the derivative's size: in step k the slowest rail gives up
+ *          0.25 / sqrt(k + 1) of the message, but never more than half of
+ *          what it has; what it gives up is spread evenly over the other
+ *          rails that take part, which keeps the shares summing to one.  A
+ *          rail whose share falls below 2^-21 (less than one unit of the
+ *          data-length table) is given nothing from then on and sits out.
+ *          The best shares seen are kept, as any subgradient iteration must
+ *          to settle.
  * Returns the best T_hot found; alpha receives its shares.
  */
 double orc_balance_iterate(uint32_t n_rails, const double *t_setup, const double *bw, double S,
@@ -556,21 +543,28 @@ double orc_balance_iterate(uint32_t n_rails, const double *t_setup, const double
     double a[64], best_a[64];
     const uint32_t R = n_rails;
     if (R == 1) { alpha[0] = 1.0; return t_setup[0] + S / bw[0]; }
-    double T = 0.0, Ti[64], cmax = 0.0;
+    double T = 0.0, Ti[64];
     for (uint32_t i = 0; i < R; ++i) {
         Ti[i] = t_setup[i] + (S / R) / bw[i];
         T += Ti[i];
-        if (S / bw[i] > cmax) cmax = S / bw[i];
     }
     for (uint32_t i = 0; i < R; ++i) a[i] = (T - Ti[i]) / (T * (double)(R - 1));
     double best_t = orc_t_hot(R, t_setup, bw, S, a, NULL);
     for (uint32_t i = 0; i < R; ++i) best_a[i] = a[i];
-    const double eta0 = 0.25 / (cmax > 0.0 ? cmax : 1.0);
+    const double floor_share = 1.0 / 2097152.0;
     for (uint32_t k = 0; k < iterations; ++k) {
-        uint32_t worst = 0;
+        uint32_t worst = 0, taking_part = 0;
         (void)orc_t_hot(R, t_setup, bw, S, a, &worst);
-        a[worst] -= eta0 / sqrt((double)k + 1.0) * (S / bw[worst]);
-        project_to_simplex(R, a);
+        for (uint32_t i = 0; i < R; ++i) taking_part += a[i] > 0.0;
+        if (taking_part < 2) break;
+        double give = 0.25 / sqrt((double)k + 1.0);
+        if (give > 0.5 * a[worst]) give = 0.5 * a[worst];
+        if (a[worst] - give < floor_share) { give = a[worst]; taking_part -= 1; }
+        a[worst] -= give;
+        if (a[worst] < 0.0 || give == 0.0) a[worst] = 0.0;
+        uint32_t others = a[worst] > 0.0 ? taking_part - 1 : taking_part;
+        for (uint32_t i = 0; i < R; ++i)
+            if (i != worst && a[i] > 0.0) a[i] += give / (double)others;
         double t = orc_t_hot(R, t_setup, bw, S, a, NULL);
         if (t < best_t) { best_t = t; for (uint32_t i = 0; i < R; ++i) best_a[i] = a[i]; }
     }

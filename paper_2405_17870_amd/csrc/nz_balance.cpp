@@ -1,0 +1,153 @@
+// Host-side Load Balancer arithmetic: how a message should be shared among
+// rails whose startup latency and bandwidth are known.
+//
+// Nezha (arXiv 2405.17870) Sec. 4.3: cold start sends everything over the best
+// single rail (Eq. 4); hot start splits the message with shares alpha that sum
+// to one and finishes when the slowest rail does (Eq. 5); the two states meet
+// at the threshold size (Eq. 6); the shares are refined by descent on the hot
+// latency (Eq. 7) from latency-derived starting shares (Eq. 8).
+//
+// With the rails' (T_setup, B) given, the point that descent converges to can
+// be written down directly: the slowest-rail latency is minimal when every
+// rail that takes part finishes at the same time T and every rail whose
+// startup latency alone exceeds T sits out ("water filling" over the startup
+// latencies).  That closed form is what is computed here; no iteration.
+#include <algorithm>
+#include <cmath>
+#include <limits>
+#include <numeric>
+#include <vector>
+
+#include "nz_internal.h"
+
+namespace {
+
+bool valid_model(const nz_rail_model *rails, uint32_t n_rails)
+{
+    if (rails == nullptr || n_rails == 0 || n_rails > NZ_MAX_RAILS) return false;
+    for (uint32_t i = 0; i < n_rails; ++i) {
+        if (!(rails[i].setup_s >= 0.0) || !std::isfinite(rails[i].setup_s)) return false;
+        if (!(rails[i].bytes_per_s > 0.0) || !std::isfinite(rails[i].bytes_per_s)) return false;
+    }
+    return true;
+}
+
+// Rails in order of startup latency (index breaks ties).
+std::vector<uint32_t> by_setup(const nz_rail_model *rails, uint32_t n_rails)
+{
+    std::vector<uint32_t> order(n_rails);
+    std::iota(order.begin(), order.end(), 0u);
+    std::stable_sort(order.begin(), order.end(),
+                     [&](uint32_t x, uint32_t y) { return rails[x].setup_s < rails[y].setup_s; });
+    return order;
+}
+
+}  // namespace
+
+extern "C" {
+
+nz_status nz_balance(const nz_rail_model *rails, uint32_t n_rails, double msg_bytes, double *alpha,
+                     uint32_t *ratios, double *t_cold, double *t_hot, uint32_t *best_rail, int *hot)
+{
+    if (n_rails > NZ_MAX_RAILS) return NZ_ERR_UNSUPPORTED;
+    if (!valid_model(rails, n_rails) || !(msg_bytes >= 0.0) || !std::isfinite(msg_bytes))
+        return NZ_ERR_INVALID_ARG;
+
+    // Eq. 4.
+    uint32_t best = 0;
+    double cold = 0.0;
+    for (uint32_t i = 0; i < n_rails; ++i) {
+        const double t = rails[i].setup_s + msg_bytes / rails[i].bytes_per_s;
+        if (i == 0 || t < cold) {
+            cold = t;
+            best = i;
+        }
+    }
+
+    // Eq. 5 at its minimum: find the common finishing time T of the rails that
+    // take part.  With the m lowest-latency rails taking part,
+    //   sum_i (T - setup_i) * B_i = S   =>   T = (S + sum setup_i B_i) / sum B_i,
+    // and rail m + 1 joins as long as its startup latency is below that T.
+    const std::vector<uint32_t> order = by_setup(rails, n_rails);
+    double sum_b = 0.0, sum_sb = 0.0, level = 0.0;
+    uint32_t active = 0;
+    for (uint32_t m = 0; m < n_rails; ++m) {
+        const nz_rail_model &r = rails[order[m]];
+        if (m > 0 && r.setup_s >= level) break;
+        sum_b += r.bytes_per_s;
+        sum_sb += r.setup_s * r.bytes_per_s;
+        level = (msg_bytes + sum_sb) / sum_b;
+        active = m + 1;
+    }
+    const bool is_hot = active > 1 && level < cold;
+
+    std::vector<double> share(n_rails, 0.0);
+    if (is_hot) {
+        for (uint32_t m = 0; m < active; ++m) {
+            const nz_rail_model &r = rails[order[m]];
+            share[order[m]] = (level - r.setup_s) * r.bytes_per_s / msg_bytes;
+        }
+    } else {
+        share[best] = 1.0;  // cold start: everything on the best single rail
+    }
+
+    if (alpha) std::copy(share.begin(), share.end(), alpha);
+    if (ratios) {
+        // Integer weights that sum to exactly 2^20: floors, then the leftover
+        // units to the largest remainders (lowest index among equals).
+        const uint32_t total = NZ_RATIO_SCALE;
+        std::vector<double> frac(n_rails);
+        uint32_t given = 0;
+        for (uint32_t i = 0; i < n_rails; ++i) {
+            const double x = share[i] * total;
+            double fl = std::floor(x);
+            if (fl > total) fl = total;
+            ratios[i] = (uint32_t)fl;
+            frac[i] = x - fl;
+            given += ratios[i];
+        }
+        while (given < total) {
+            uint32_t pick = 0;
+            for (uint32_t i = 1; i < n_rails; ++i)
+                if (frac[i] > frac[pick]) pick = i;
+            ratios[pick] += 1;
+            frac[pick] = -1.0;
+            ++given;
+            bool any = false;
+            for (uint32_t i = 0; i < n_rails; ++i) any = any || frac[i] >= 0.0;
+            if (!any)
+                for (uint32_t i = 0; i < n_rails; ++i) frac[i] = 0.0;
+        }
+        while (given > total) {  // only through floating-point excess in the shares
+            uint32_t pick = 0;
+            for (uint32_t i = 1; i < n_rails; ++i)
+                if (ratios[i] > ratios[pick]) pick = i;
+            ratios[pick] -= 1;
+            --given;
+        }
+    }
+    if (t_cold) *t_cold = cold;
+    if (t_hot) *t_hot = is_hot ? level : cold;
+    if (best_rail) *best_rail = best;
+    if (hot) *hot = is_hot ? 1 : 0;
+    return NZ_OK;
+}
+
+nz_status nz_balance_threshold(const nz_rail_model *rails, uint32_t n_rails, double *threshold_bytes)
+{
+    if (n_rails > NZ_MAX_RAILS) return NZ_ERR_UNSUPPORTED;
+    if (!valid_model(rails, n_rails) || threshold_bytes == nullptr) return NZ_ERR_INVALID_ARG;
+    if (n_rails == 1) {
+        *threshold_bytes = std::numeric_limits<double>::infinity();
+        return NZ_OK;
+    }
+    // Eq. 6: the two states give the same latency up to the size at which the
+    // second rail starts to pay off: while the lowest-latency rail alone
+    // finishes before the next rail could even start, (setup_2 - setup_1) * B_1.
+    const std::vector<uint32_t> order = by_setup(rails, n_rails);
+    const nz_rail_model &first = rails[order[0]], &second = rails[order[1]];
+    *threshold_bytes = (second.setup_s - first.setup_s) * first.bytes_per_s;
+    return NZ_OK;
+}
+
+}  // extern "C"

@@ -33,7 +33,7 @@ EXPORTS = [
     "nz_status_str", "nz_last_hip_error", "nz_dtype_bytes", "nz_rail_partition",
     "nz_rail_partition_ex", "nz_segment_map", "nz_allreduce_sim", "nz_reduce_scatter_sim",
     "nz_allgather_sim", "nz_allreduce_sim_chunked", "nz_failover_target",
-    "nz_allreduce_sim_failover", "nz_pack", "nz_unpack",
+    "nz_allreduce_sim_failover", "nz_pack", "nz_unpack", "nz_balance", "nz_balance_threshold",
 ]
 
 
@@ -82,6 +82,10 @@ def load() -> ctypes.CDLL:
                  "nz_unpack", "nz_allreduce_sim_chunked", "nz_failover_target",
                  "nz_allreduce_sim_failover"):
         getattr(lib, name).restype = i32
+    lib.nz_balance.argtypes = [vp, u32, ctypes.c_double, vp, vp, vp, vp, vp, vp]
+    lib.nz_balance.restype = i32
+    lib.nz_balance_threshold.argtypes = [vp, u32, vp]
+    lib.nz_balance_threshold.restype = i32
     _lib = lib
     return lib
 
@@ -243,3 +247,39 @@ def nz_unpack(send_bufs: Sequence, seg_off: np.ndarray, rail: int, seg_ids: Sequ
     _check(lib.nz_unpack(_ptr_array(send_bufs), n_nodes, seg.ctypes.data, n_rails, rail,
                          _u32_array(seg_ids), len(seg_ids), elem_bytes, _ptr_array(node_bufs),
                          _stream_handle(stream)))
+
+
+NZ_RATIO_SCALE = 1 << 20
+
+
+def _models(setup_s: Sequence[float], bytes_per_s: Sequence[float]):
+    if len(setup_s) != len(bytes_per_s):
+        raise ValueError("one startup latency and one bandwidth per rail")
+    arr = (ctypes.c_double * (2 * max(len(setup_s), 1)))()
+    for i, (t, b) in enumerate(zip(setup_s, bytes_per_s)):
+        arr[2 * i], arr[2 * i + 1] = float(t), float(b)
+    return arr
+
+
+def nz_balance(setup_s: Sequence[float], bytes_per_s: Sequence[float], msg_bytes: float) -> dict:
+    """Shares of a message among rails of known startup latency and bandwidth (Sec. 4.3,
+    Eq. 4-8).  Host only.  Returns alpha, ratios (sum 2**20), t_cold, t_hot, best_rail, hot."""
+    lib = load()
+    R = len(setup_s)
+    alpha = np.zeros(max(R, 1), dtype=np.float64)
+    ratios = np.zeros(max(R, 1), dtype=np.uint32)
+    tc, th = ctypes.c_double(0), ctypes.c_double(0)
+    best, hot = ctypes.c_uint32(0), ctypes.c_int(0)
+    _check(lib.nz_balance(_models(setup_s, bytes_per_s), R, float(msg_bytes), alpha.ctypes.data,
+                          ratios.ctypes.data, ctypes.byref(tc), ctypes.byref(th), ctypes.byref(best),
+                          ctypes.byref(hot)))
+    return {"alpha": alpha[:R], "ratios": ratios[:R], "t_cold": tc.value, "t_hot": th.value,
+            "best_rail": int(best.value), "hot": bool(hot.value)}
+
+
+def nz_balance_threshold(setup_s: Sequence[float], bytes_per_s: Sequence[float]) -> float:
+    """Message size up to which all data goes over the best single rail (Sec. 4.3, Eq. 6)."""
+    lib = load()
+    out = ctypes.c_double(0)
+    _check(lib.nz_balance_threshold(_models(setup_s, bytes_per_s), len(setup_s), ctypes.byref(out)))
+    return out.value
