@@ -40,7 +40,8 @@ def parse_args():
     p.add_argument("--workload", default="c4", help="c1, c1_i32, c2, c3, c4 (default), c5")
     p.add_argument("--parts", default="fused,ring,pack,unpack",
                    help="comma list of parts to run in a step (default: all four); also available: "
-                        "rs, ag = fused reduce-scatter-only / allgather-only")
+                        "rs, ag = fused reduce-scatter-only / allgather-only; chunked = Ring_Chunked; "
+                        "failover = fused allreduce with the last rail failing")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--placement", default="spread", choices=["spread", "packed", "torch"],
                    help="where the buffers live in HBM: spread = inputs in the first 96 GiB region, "
@@ -51,6 +52,10 @@ def parse_args():
                         "the inputs' HBM region (reported as fused_with_outputs_in_one_region)")
     p.add_argument("--packed-offset-gib", type=float, default=0.0,
                    help="with --placement packed: arena offset at which the buffers start")
+    p.add_argument("--chunk-elems", type=int, default=1 << 20,
+                   help="piece length of the optional part 'chunked' (Ring_Chunked)")
+    p.add_argument("--graph", action="store_true",
+                   help="capture one step in a HIP graph and time its replays (no per-part times)")
     p.add_argument("--cpu-sample-elems", type=int, default=8 * 1024 * 1024)
     return p.parse_args()
 
@@ -177,7 +182,9 @@ def main() -> int:
 
     alg_bytes = {"fused": 2 * N * S, "ring": 5 * (N - 1) * S, "pack": 2 * N * S, "unpack": 2 * N * S,
                  # optional parts: the two halves on their own, fused form
-                 "rs": (N + 1) * S, "ag": N * S}
+                 "rs": (N + 1) * S, "ag": N * S,
+                 # Ring_Chunked moves the ring's bytes in more launches; failover the fused bytes in two
+                 "chunked": 5 * (N - 1) * S, "failover": 2 * N * S}
 
     def run_part(p):
         if p == "fused":
@@ -188,6 +195,10 @@ def main() -> int:
             nz.nz_reduce_scatter_sim(ins, n, w.ratios, w.dtype, "fused", outs)
         elif p == "ag":
             nz.nz_allgather_sim(outs, n, w.ratios, w.dtype, "fused")
+        elif p == "chunked":
+            nz.nz_allreduce_sim_chunked(ins, n, w.ratios, w.dtype, args.chunk_elems, outs)
+        elif p == "failover":
+            nz.nz_allreduce_sim_failover(ins, n, w.ratios, w.dtype, "fused", outs, R - 1)
         elif p == "pack":
             for k in range(R):
                 nz.nz_pack(ins, seg, k, ids, e, send[k], send[k][0].numel() * e)
@@ -212,29 +223,48 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     events = {p: [] for p in parts}
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step(events)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    if args.graph:
+        # The library launches plain kernels on the given stream and touches no
+        # device memory of its own, so a step can be captured as it is.
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        for p in parts:            # no events inside a graph: share the step time by bytes
+            share = wall * 1e3 / args.steps * alg_bytes[p] / sum(alg_bytes[q] for q in parts)
+            events[p] = share
+    else:
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            step(events)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
 
     ms_per_step = wall * 1e3 / args.steps
     step_bytes = sum(alg_bytes[p] for p in parts)
     part_stats = {}
     for p in parts:
-        ms = sum(a.elapsed_time(b) for a, b in events[p]) / len(events[p])
+        ms = events[p] if args.graph else sum(a.elapsed_time(b) for a, b in events[p]) / len(events[p])
         gbs = alg_bytes[p] / (ms * 1e-3) / 1e9
         part_stats[p] = {"ms": round(ms, 4), "payload_GBps": round(S / (ms * 1e-3) / 1e9, 2),
                          "hbm_GBps": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
                          "algorithmic_bytes": alg_bytes[p]}
 
     head = "fused" if "fused" in parts else parts[0]
-    launches = {"fused": 1, "ring": 2 * (N - 1), "pack": R, "unpack": R, "rs": 1, "ag": 1}[head]
+    launches = {"fused": 1, "ring": 2 * (N - 1), "pack": R, "unpack": R, "rs": 1, "ag": 1,
+                "chunked": 2 * (N - 1), "failover": 2}[head]
     achieved = part_stats[head]["hbm_GBps"]
     roofline = {
         "kernel": {"fused": "nz_fused_reduce_bcast", "ring": "nz_ring_step",
                    "pack": "nz_segment_copy", "unpack": "nz_segment_copy",
-                   "rs": "nz_fused_reduce_bcast", "ag": "nz_gather_bcast"}[head],
+                   "rs": "nz_fused_reduce_bcast", "ag": "nz_gather_bcast",
+                   "chunked": "nz_ring_step", "failover": "nz_fused_reduce_bcast"}[head],
         "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
         "algorithmic_bytes_per_launch": alg_bytes[head] // launches,
@@ -253,7 +283,8 @@ def main() -> int:
         "config": {"workload": f"{w.name}: {N} simulated nodes x {n} {w.dtype} elements, "
                                f"rails {':'.join(map(str, w.ratios))}",
                    "storage_dtype": w.dtype, "n_nodes": N, "n_elems": n, "ratios": list(w.ratios),
-                   "parts": parts, "distinct_outputs": N, "placement": placement_note},
+                   "parts": parts, "distinct_outputs": N, "placement": placement_note,
+                   "hip_graph": bool(args.graph)},
         "pct_of_hbm_peak": round(100.0 * step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
         "parts": part_stats,
         "roofline": roofline,
