@@ -52,6 +52,8 @@ WORKLOADS = {
     "c2": Workload("c2", 8, 25_557_032, "f32", (100, 40), 1e-3, seed=SEED_BASE + 2),
     "c3": Workload("c3", 8, 138_357_544, "bf16", (100, 100, 40), 1e-3, outlier_frac=0.01,
                    seed=SEED_BASE + 3),
+    "c3_f16": Workload("c3_f16", 8, 138_357_544, "f16", (100, 100, 40), 1e-3, outlier_frac=0.01,
+                       seed=SEED_BASE + 6),
     "c4": Workload("c4", 32, 335_000_000, "bf16", (100, 25), 1e-3, seed=SEED_BASE + 4),
     "c5": Workload("c5", 128, 16_777_216, "f32", (100, 100, 40, 10), 1e-2, seed=SEED_BASE + 5),
 }

@@ -52,15 +52,16 @@ def test_full_compare_both_modes(orc, name):
     gu.check_fused_against_oracle(orc, w.dtype, inputs.to_host_storage(outs[0]), host, name + " ring")
 
 
-def test_c3_bf16_outliers_full_compare(orc):
-    w = inputs.WORKLOADS["c3"]
-    _say("c3: generating")
+@pytest.mark.parametrize("name", ["c3", "c3_f16"])
+def test_c3_16bit_outliers_full_compare(orc, name):
+    w = inputs.WORKLOADS[name]
+    _say(f"{name}: generating")
     ins = inputs.workload_buffers(w, device=gu.DEV)
     outs = _run(w, "fused", ins)
     assert _all_equal(outs)
     _say("c3: oracle")
     host = [inputs.to_host_storage(t) for t in ins]
-    n_escape = gu.check_fused_against_oracle(orc, "bf16", inputs.to_host_storage(outs[0]), host, "c3")
+    n_escape = gu.check_fused_against_oracle(orc, w.dtype, inputs.to_host_storage(outs[0]), host, name)
     _say(f"c3: elements judged by the cancellation clause: {n_escape} of {w.n_elems}")
     assert n_escape <= w.n_elems // 1_000_000
 
