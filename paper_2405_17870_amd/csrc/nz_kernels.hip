@@ -253,6 +253,15 @@ struct VecPacket {
     {
         __builtin_nontemporal_store(v, (NZ_GLOBAL vec16 *)(static_cast<char *>(base) + byte_off));
     }
+    // Ordinary (cache-allocating) forms, for data the next launch reads again.
+    static __device__ __forceinline__ raw_t load_again(const void *base, u64 byte_off)
+    {
+        return *(const NZ_GLOBAL vec16 *)(static_cast<const char *>(base) + byte_off);
+    }
+    static __device__ __forceinline__ void store_for_reuse(void *base, u64 byte_off, const raw_t &v)
+    {
+        *(NZ_GLOBAL vec16 *)(static_cast<char *>(base) + byte_off) = v;
+    }
     static __device__ __forceinline__ void widen(const raw_t &r, typename T::acc_t (&a)[kLanes])
     {
         T::widen(r, a);
@@ -279,6 +288,14 @@ struct ElemPacket {
     static __device__ __forceinline__ void store(void *base, u64 byte_off, const raw_t &v)
     {
         *(NZ_GLOBAL raw_t *)(static_cast<char *>(base) + byte_off) = v;
+    }
+    static __device__ __forceinline__ raw_t load_again(const void *base, u64 byte_off)
+    {
+        return load(base, byte_off);
+    }
+    static __device__ __forceinline__ void store_for_reuse(void *base, u64 byte_off, const raw_t &v)
+    {
+        store(base, byte_off, v);
     }
     static __device__ __forceinline__ void widen(const raw_t &r, typename T::acc_t (&a)[1])
     {
@@ -454,24 +471,31 @@ struct RingArgs {
 // in step 0 and the partial it stored in step s - 1 afterwards.
 // Allgather step s: node r sends the complete segment (r + 1 - s) mod N; d
 // overwrites its copy.
-template <class T, class P, bool GATHER>
+//
+// What a step stores is what the next step sends.  REUSE = the bytes of one
+// step fit the last-level cache: they are stored and re-read with ordinary,
+// cache-allocating accesses; otherwise they stream past the caches.
+template <class T, class P, bool GATHER, bool REUSE>
 __device__ __forceinline__ void ring_at(const void *sent, const void *own, void *dst, u64 byte_off)
 {
-    if (GATHER) {
-        P::store(dst, byte_off, P::load(sent, byte_off));
-    } else {
+    const typename P::raw_t rs = REUSE ? P::load_again(sent, byte_off) : P::load(sent, byte_off);
+    typename P::raw_t result = rs;
+    if (!GATHER) {
         typename T::acc_t x[P::kLanes], y[P::kLanes];
-        const typename P::raw_t rs = P::load(sent, byte_off);
         const typename P::raw_t ro = P::load(own, byte_off);
         P::widen(rs, x);
         P::widen(ro, y);
 #pragma unroll
         for (int l = 0; l < P::kLanes; ++l) x[l] = x[l] + y[l];
-        P::store(dst, byte_off, P::narrow(x));
+        result = P::narrow(x);
     }
+    if (REUSE)
+        P::store_for_reuse(dst, byte_off, result);
+    else
+        P::store(dst, byte_off, result);
 }
 
-template <class T, int ITERS, bool GATHER>
+template <class T, int ITERS, bool GATHER, bool REUSE>
 __global__ __launch_bounds__(kThreads) void nz_ring_step(const RingArgs)
 {
     const NZ_KARG RingArgs &a = kernel_args<RingArgs>();
@@ -494,16 +518,16 @@ __global__ __launch_bounds__(kThreads) void nz_ring_step(const RingArgs)
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         const u64 vec = t.tile_base + (u64)it * kThreads + threadIdx.x;
-        if (vec >= lo && vec < hi) ring_at<T, VecPacket<T>, GATHER>(sent, own, dst, vec << 4);
+        if (vec >= lo && vec < hi) ring_at<T, VecPacket<T>, GATHER, REUSE>(sent, own, dst, vec << 4);
     }
     const u64 head_end = (full_lo << 4) < t.b1 ? (full_lo << 4) : t.b1;
     u64 tail_beg = full_hi << 4;
     if (tail_beg < head_end) tail_beg = head_end;
     const u64 eoff = (u64)threadIdx.x << T::kShift;
     if (t.vec_lo == (t.b0 >> 4) && t.b0 + eoff < head_end)
-        ring_at<T, ElemPacket<T>, GATHER>(sent, own, dst, t.b0 + eoff);
+        ring_at<T, ElemPacket<T>, GATHER, REUSE>(sent, own, dst, t.b0 + eoff);
     if (t.vec_hi == ((t.b1 + 15) >> 4) && tail_beg + eoff < t.b1)
-        ring_at<T, ElemPacket<T>, GATHER>(sent, own, dst, tail_beg + eoff);
+        ring_at<T, ElemPacket<T>, GATHER, REUSE>(sent, own, dst, tail_beg + eoff);
 }
 
 // Direct allgather: every segment is read once from the node that owns it
@@ -801,15 +825,19 @@ enum Collective { kAllreduce, kReduceScatter, kAllgather };
 
 // n_pieces > 1: every step is issued as n_pieces launches, piece c of every
 // segment before piece c + 1 (a.g.win_len elements each).
-template <class T>
-nz_status launch_ring(RingArgs &a, u32 blocks, hipStream_t st, Collective what, u64 n_pieces)
+// Bytes of one ring step up to which the step's output is kept in cache for
+// the next step to read (half of the 256 MB last-level cache).
+constexpr u64 kRingReuseBytes = 128ull << 20;
+
+template <class T, bool REUSE>
+nz_status launch_ring_steps(RingArgs &a, u32 blocks, hipStream_t st, Collective what, u64 n_pieces)
 {
     const u32 N = a.g.n_nodes;
     for (u32 s = 0; s + 1 < N && what != kAllgather; ++s) {
         a.step = s;
         for (u64 c = 0; c < n_pieces; ++c) {
             a.g.win_off = c * (n_pieces > 1 ? a.g.win_len : 0);
-            hipLaunchKernelGGL((nz_ring_step<T, kRingIters, false>), dim3(blocks), dim3(kThreads), 0, st, a);
+            hipLaunchKernelGGL((nz_ring_step<T, kRingIters, false, REUSE>), dim3(blocks), dim3(kThreads), 0, st, a);
             const hipError_t e = hipGetLastError();
             if (e != hipSuccess) return hip_failed(e, "ring reduce-scatter launch");
         }
@@ -818,12 +846,20 @@ nz_status launch_ring(RingArgs &a, u32 blocks, hipStream_t st, Collective what, 
         a.step = s;
         for (u64 c = 0; c < n_pieces; ++c) {
             a.g.win_off = c * (n_pieces > 1 ? a.g.win_len : 0);
-            hipLaunchKernelGGL((nz_ring_step<T, kRingIters, true>), dim3(blocks), dim3(kThreads), 0, st, a);
+            hipLaunchKernelGGL((nz_ring_step<T, kRingIters, true, REUSE>), dim3(blocks), dim3(kThreads), 0, st, a);
             const hipError_t e = hipGetLastError();
             if (e != hipSuccess) return hip_failed(e, "ring allgather launch");
         }
     }
     return NZ_OK;
+}
+
+template <class T>
+nz_status launch_ring(RingArgs &a, u32 blocks, hipStream_t st, Collective what, u64 n_pieces)
+{
+    const u64 step_bytes = (a.g.off[a.g.n_rails] - a.g.off[0]) << a.elem_shift;
+    return step_bytes <= kRingReuseBytes ? launch_ring_steps<T, true>(a, blocks, st, what, n_pieces)
+                                         : launch_ring_steps<T, false>(a, blocks, st, what, n_pieces);
 }
 
 template <class T>
