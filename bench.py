@@ -54,6 +54,9 @@ def parse_args():
                    help="with --placement packed: arena offset at which the buffers start")
     p.add_argument("--chunk-elems", type=int, default=1 << 20,
                    help="piece length of the optional part 'chunked' (Ring_Chunked)")
+    p.add_argument("--pack-order", default="rail", choices=["rail", "ring"],
+                   help="segment list of pack/unpack: the whole rail in order (one aligned run per "
+                        "node) or the order a node sends its segments in (misaligned runs: LDS path)")
     p.add_argument("--graph", action="store_true",
                    help="capture one step in a HIP graph and time its replays (no per-part times)")
     p.add_argument("--cpu-sample-elems", type=int, default=8 * 1024 * 1024)
@@ -177,7 +180,7 @@ def main() -> int:
         outs = [torch.empty_like(t) for t in ins]
         send = [[torch.zeros(rail_len[k], dtype=tdtype, device=dev) for _ in range(N)] for k in range(R)] \
             if need_send else []
-    ids = list(range(N))
+    ids = list(range(N)) if args.pack_order == "rail" else [(N // 2 - s) % N for s in range(N)]
     torch.cuda.synchronize()
 
     alg_bytes = {"fused": 2 * N * S, "ring": 5 * (N - 1) * S, "pack": 2 * N * S, "unpack": 2 * N * S,

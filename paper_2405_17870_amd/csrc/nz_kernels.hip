@@ -574,7 +574,7 @@ __global__ __launch_bounds__(kThreads) void nz_gather_bcast(const RingArgs)
 // Segment copy (pack / unpack)
 // ---------------------------------------------------------------------------
 
-constexpr int kCopyMaxRuns = 40;  // runs per launch; longer lists take several launches
+constexpr int kCopyMaxRuns = 64;  // runs per launch; longer lists take several launches
 #ifndef NZ_COPY_ITERS
 #define NZ_COPY_ITERS 2
 #endif
@@ -594,25 +594,45 @@ struct CopyArgs {
     void *dst[NZ_MAX_NODES];
 };
 
+template <class E>
+__device__ __forceinline__ void copy_elem(char *dst, const char *src)
+{
+    *(NZ_GLOBAL E *)dst = *(const NZ_GLOBAL E *)src;
+}
+
 // Tiles lie on the destination's 16-byte grid, so every store is an aligned
 // 16-byte store.  When the source of a run sits at another offset within its
-// 16 bytes (shift != 0), the workgroup stages the aligned source vectors that
-// cover its tile in LDS and each thread assembles its destination vector from
-// five consecutive 32-bit LDS words; with shift == 0 it is a plain vector copy.
-// Bytes of the run outside whole destination vectors, and destination vectors
-// whose source words are not all inside the run, are copied element by
-// element, so no access ever leaves [off, off + len) of either buffer.
+// 16 bytes (shift != 0), each lane loads the aligned source vector that holds
+// the first bytes it needs, takes the following vector from the next lane
+// through the LDS crossbar (ds_bpermute: no LDS memory, no barrier; the last
+// lane of a wave loads its second vector itself) and assembles its
+// destination vector with byte-align operations.  With shift == 0 it is a
+// plain vector copy.  Bytes of the run outside whole destination vectors, and
+// destination vectors whose two source vectors are not both inside the run,
+// are copied element by element, so no access ever leaves [off, off + len) of
+// either buffer.
+//
+// ALIGNED_ONLY: the host saw that every run of the launch has shift == 0 (a
+// whole rail always has); the exchange path is then compiled out.
+template <bool ALIGNED_ONLY>
 __global__ __launch_bounds__(kThreads) void nz_segment_copy(const CopyArgs)
 {
     const NZ_KARG CopyArgs &a = kernel_args<CopyArgs>();
-    __shared__ vec16 stage[kThreads + 1];
 
     // Node index fastest: the workgroups in flight at one time cover the same
     // tiles of many nodes' buffers rather than one buffer end to end.
     const u32 per_node = blockIdx.x / a.n_nodes;
     const u32 node = blockIdx.x - per_node * a.n_nodes;
     u32 run = 0;
-    while (run + 1 < a.n_runs && per_node >= a.tile0[run + 1]) ++run;
+    for (u32 span = a.n_runs; span > 1;) {  // last run whose first workgroup is <= per_node
+        const u32 half = span >> 1;
+        if (per_node >= a.tile0[run + half]) {
+            run += half;
+            span -= half;
+        } else {
+            span = half;
+        }
+    }
     const u32 tile = per_node - a.tile0[run];
 
     const char *src = static_cast<const char *>(a.src[node]);
@@ -620,61 +640,84 @@ __global__ __launch_bounds__(kThreads) void nz_segment_copy(const CopyArgs)
     const u64 S = a.src_off[run], D = a.dst_off[run], L = a.len[run];
     const u64 d_end = D + L;
     const u64 full_lo = (D + 15) >> 4, full_hi = d_end >> 4;  // whole destination vectors
-    const u32 shift = (u32)((S - D) & 15);
+    const u32 shift = ALIGNED_ONLY ? 0u : (u32)((S - D) & 15);
     // Aligned source vectors that lie wholly inside the run.
-    const u64 src_full_lo = (S + 15) >> 4, src_full_hi = (S + L) >> 4;
+    const long long src_full_lo = (long long)((S + 15) >> 4), src_full_hi = (long long)((S + L) >> 4);
+    const u32 lane = threadIdx.x & 63u;
 
     constexpr int TILE = kCopyIters * kThreads;
     const u64 tile_base = ((D >> 4) / TILE + tile) * (u64)TILE;
 
+    if (shift == 0) {
+        // One sub-tile at a time: load, store, next (measured faster than batching the loads).
 #pragma unroll 1
-    for (int it = 0; it < kCopyIters; ++it) {
-        const u64 sub = tile_base + (u64)it * kThreads;  // first destination vector of the sub-tile
-        if (sub >= ((d_end + 15) >> 4)) break;           // uniform: past the run
-        const u64 w = sub + threadIdx.x;
-        const bool whole = (w >= full_lo && w < full_hi);
-        if (shift == 0) {
-            if (whole) {
+        for (int it = 0; it < kCopyIters; ++it) {
+            const u64 w = tile_base + (u64)it * kThreads + threadIdx.x;  // destination vector
+            if (w >= full_lo && w < full_hi) {
                 const u64 sb = (w << 4) - D + S;
-                const vec16 v = __builtin_nontemporal_load(reinterpret_cast<const vec16 *>(src + sb));
-                __builtin_nontemporal_store(v, reinterpret_cast<vec16 *>(dst + (w << 4)));
+                const vec16 v = __builtin_nontemporal_load((const NZ_GLOBAL vec16 *)(src + sb));
+                __builtin_nontemporal_store(v, (NZ_GLOBAL vec16 *)(dst + (w << 4)));
             }
-            continue;
         }
-        // Source position of destination byte 16 * sub, rounded down to a vector.
-        // For the first sub-tile it can lie in front of the source buffer, hence
-        // signed arithmetic; only vectors wholly inside the run are touched.
-        const long long s_first = (long long)(sub << 4) - (long long)D + (long long)S;
-        const long long sv0 = (s_first - (long long)shift) >> 4;  // exact: s_first = shift mod 16
-        __syncthreads();                                          // previous sub-tile's readers are done
-        for (u32 i = threadIdx.x; i < kThreads + 1; i += kThreads) {
-            const long long sv = sv0 + i;
-            if (sv >= (long long)src_full_lo && sv < (long long)src_full_hi)
-                stage[i] = __builtin_nontemporal_load(reinterpret_cast<const vec16 *>(src + (sv << 4)));
-        }
-        __syncthreads();
-        const long long sv = sv0 + threadIdx.x;
-        const bool staged = whole && sv >= (long long)src_full_lo && sv + 1 < (long long)src_full_hi;
-        if (staged) {
-            const u32 *words = reinterpret_cast<const u32 *>(stage) + threadIdx.x * 4 + (shift >> 2);
-            const u32 w0 = words[0], w1 = words[1], w2 = words[2], w3 = words[3], w4 = words[4];
+    }
+#pragma unroll 1
+    for (int it = 0; it < (!ALIGNED_ONLY && shift != 0 ? kCopyIters : 0); ++it) {
+        const u64 w = tile_base + (u64)it * kThreads + threadIdx.x;  // destination vector
+        const bool whole = (w >= full_lo && w < full_hi);
+        // Source position of this destination vector; its first byte lies in
+        // aligned source vector sv, its last in sv + 1.  (For the first tile the
+        // position can lie in front of the buffer, hence signed arithmetic; only
+        // vectors wholly inside the run are loaded.)
+        const long long s_pos = (long long)(w << 4) - (long long)D + (long long)S;
+        const long long sv = (s_pos - (long long)shift) >> 4;  // exact: s_pos = shift mod 16
+        vec16 lo = {0, 0, 0, 0}, hi = {0, 0, 0, 0};
+        if (sv >= src_full_lo && sv < src_full_hi)
+            lo = __builtin_nontemporal_load((const NZ_GLOBAL vec16 *)(src + (sv << 4)));
+        // Every lane takes part in the exchange, whatever it loaded.
+        hi.x = __shfl_down(lo.x, 1);
+        hi.y = __shfl_down(lo.y, 1);
+        hi.z = __shfl_down(lo.z, 1);
+        hi.w = __shfl_down(lo.w, 1);
+        const bool both = whole && sv >= src_full_lo && sv + 1 < src_full_hi;
+        if (lane == 63 && both) hi = __builtin_nontemporal_load((const NZ_GLOBAL vec16 *)(src + ((sv + 1) << 4)));
+        if (both) {
+            const u32 word[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
             const u32 sh = shift & 3;  // 0 or 2 bytes
             vec16 v;
-            v.x = __builtin_amdgcn_alignbyte(w1, w0, sh);
-            v.y = __builtin_amdgcn_alignbyte(w2, w1, sh);
-            v.z = __builtin_amdgcn_alignbyte(w3, w2, sh);
-            v.w = __builtin_amdgcn_alignbyte(w4, w3, sh);
-            __builtin_nontemporal_store(v, reinterpret_cast<vec16 *>(dst + (w << 4)));
+            switch (shift >> 2) {  // uniform
+            case 0:  // shift == 2
+                v.x = __builtin_amdgcn_alignbyte(word[1], word[0], sh);
+                v.y = __builtin_amdgcn_alignbyte(word[2], word[1], sh);
+                v.z = __builtin_amdgcn_alignbyte(word[3], word[2], sh);
+                v.w = __builtin_amdgcn_alignbyte(word[4], word[3], sh);
+                break;
+            case 1:
+                v.x = __builtin_amdgcn_alignbyte(word[2], word[1], sh);
+                v.y = __builtin_amdgcn_alignbyte(word[3], word[2], sh);
+                v.z = __builtin_amdgcn_alignbyte(word[4], word[3], sh);
+                v.w = __builtin_amdgcn_alignbyte(word[5], word[4], sh);
+                break;
+            case 2:
+                v.x = __builtin_amdgcn_alignbyte(word[3], word[2], sh);
+                v.y = __builtin_amdgcn_alignbyte(word[4], word[3], sh);
+                v.z = __builtin_amdgcn_alignbyte(word[5], word[4], sh);
+                v.w = __builtin_amdgcn_alignbyte(word[6], word[5], sh);
+                break;
+            default:
+                v.x = __builtin_amdgcn_alignbyte(word[4], word[3], sh);
+                v.y = __builtin_amdgcn_alignbyte(word[5], word[4], sh);
+                v.z = __builtin_amdgcn_alignbyte(word[6], word[5], sh);
+                v.w = __builtin_amdgcn_alignbyte(word[7], word[6], sh);
+                break;
+            }
+            __builtin_nontemporal_store(v, (NZ_GLOBAL vec16 *)(dst + (w << 4)));
         } else if (whole) {
             // A whole destination vector at the very edge of the run's source.
             const u64 sb = (w << 4) - D + S;
             if (a.elem_bytes == 4) {
-                for (int i = 0; i < 4; ++i)
-                    reinterpret_cast<u32 *>(dst + (w << 4))[i] = reinterpret_cast<const u32 *>(src + sb)[i];
+                for (int i = 0; i < 4; ++i) copy_elem<u32>(dst + (w << 4) + 4 * i, src + sb + 4 * i);
             } else {
-                for (int i = 0; i < 8; ++i)
-                    reinterpret_cast<unsigned short *>(dst + (w << 4))[i] =
-                        reinterpret_cast<const unsigned short *>(src + sb)[i];
+                for (int i = 0; i < 8; ++i) copy_elem<unsigned short>(dst + (w << 4) + 2 * i, src + sb + 2 * i);
             }
         }
     }
@@ -688,18 +731,16 @@ __global__ __launch_bounds__(kThreads) void nz_segment_copy(const CopyArgs)
     const u64 last_tile_base = (((d_end + 15) >> 4) - 1) / TILE * (u64)TILE;
     if (tile_base == first_tile_base && D + eoff < head_end) {
         if (a.elem_bytes == 4)
-            *reinterpret_cast<u32 *>(dst + D + eoff) = *reinterpret_cast<const u32 *>(src + S + eoff);
+            copy_elem<u32>(dst + D + eoff, src + S + eoff);
         else
-            *reinterpret_cast<unsigned short *>(dst + D + eoff) =
-                *reinterpret_cast<const unsigned short *>(src + S + eoff);
+            copy_elem<unsigned short>(dst + D + eoff, src + S + eoff);
     }
     if (tile_base == last_tile_base && tail_beg + eoff < d_end) {
         const u64 sb = tail_beg + eoff - D + S;
         if (a.elem_bytes == 4)
-            *reinterpret_cast<u32 *>(dst + tail_beg + eoff) = *reinterpret_cast<const u32 *>(src + sb);
+            copy_elem<u32>(dst + tail_beg + eoff, src + sb);
         else
-            *reinterpret_cast<unsigned short *>(dst + tail_beg + eoff) =
-                *reinterpret_cast<const unsigned short *>(src + sb);
+            copy_elem<unsigned short>(dst + tail_beg + eoff, src + sb);
     }
 }
 
@@ -960,7 +1001,12 @@ nz_status segment_copy(const void *const *src, void *const *dst, u32 n_nodes, co
             a.src[m] = src[m];
             a.dst[m] = dst[m];
         }
-        hipLaunchKernelGGL(nz_segment_copy, dim3((u32)(blocks * n_nodes)), dim3(kThreads), 0, st, a);
+        bool aligned = true;
+        for (u32 i = 0; i < r; ++i) aligned = aligned && ((a.src_off[i] - a.dst_off[i]) & 15) == 0;
+        if (aligned)
+            hipLaunchKernelGGL(nz_segment_copy<true>, dim3((u32)(blocks * n_nodes)), dim3(kThreads), 0, st, a);
+        else
+            hipLaunchKernelGGL(nz_segment_copy<false>, dim3((u32)(blocks * n_nodes)), dim3(kThreads), 0, st, a);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_failed(e, "segment copy launch");
     }
