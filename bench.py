@@ -162,7 +162,7 @@ def main() -> int:
             arena.set_cursor(0, int(args.packed_offset_gib * (1 << 30)))
         ins = [arena.alloc(n, tdtype, 0) for _ in range(N)]
         outs = arena.alloc_striped(N, n, tdtype, written)
-        send = [arena.alloc_striped(N, rail_len[k], tdtype, written, start=k) for k in range(R)] \
+        send = [arena.alloc_striped(N, rail_len[k], tdtype, written, start=k + 1) for k in range(R)] \
             if need_send else []
         if args.reference_one_region and args.placement == "spread" and "fused" in parts and arena.free_in(0) >= N * (n * e + (2 << 20)):
             packed_ref_outs = [arena.alloc(n, tdtype, 0) for _ in range(N)]

@@ -483,6 +483,10 @@ __device__ __forceinline__ void ring_at(const void *sent, const void *own, void 
     if (!GATHER) {
         typename T::acc_t x[P::kLanes], y[P::kLanes];
         const typename P::raw_t ro = P::load(own, byte_off);
+        // Both loads are issued before either value is touched (left alone, the
+        // scheduler starts widening the first operand and only then issues the
+        // second load: two memory round trips instead of one).
+        __builtin_amdgcn_sched_barrier(0);
         P::widen(rs, x);
         P::widen(ro, y);
 #pragma unroll
