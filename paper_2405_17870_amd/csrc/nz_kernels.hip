@@ -760,6 +760,16 @@ nz_status hip_failed(hipError_t e, const char *what)
     return NZ_ERR_HIP;
 }
 
+// Launch a kernel whose only parameter is its argument struct and return the
+// launch's own status (hipGetLastError could hand back an older error that
+// some other code of the process left behind).
+template <class Args>
+hipError_t launch(void (*kernel)(const Args), u32 blocks, const Args &args, hipStream_t st)
+{
+    void *params[] = {const_cast<Args *>(&args)};
+    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3(blocks), dim3(kThreads), params, 0, st);
+}
+
 bool aligned256(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
 
 // Fill the geometry for tiles of tile_vecs 16-byte vectors.  Returns the
@@ -856,8 +866,7 @@ bool written_range_overlaps(std::vector<Range> &v)
 template <class T>
 nz_status launch_fused(const FusedArgs &a, u32 blocks, hipStream_t st)
 {
-    hipLaunchKernelGGL((nz_fused_reduce_bcast<T>), dim3(blocks), dim3(kThreads), 0, st, a);
-    const hipError_t e = hipGetLastError();
+    const hipError_t e = launch(nz_fused_reduce_bcast<T>, blocks, a, st);
     return e == hipSuccess ? NZ_OK : hip_failed(e, "fused reduce launch");
 }
 
@@ -882,8 +891,7 @@ nz_status launch_ring_steps(RingArgs &a, u32 blocks, hipStream_t st, Collective 
         a.step = s;
         for (u64 c = 0; c < n_pieces; ++c) {
             a.g.win_off = c * (n_pieces > 1 ? a.g.win_len : 0);
-            hipLaunchKernelGGL((nz_ring_step<T, kRingIters, false, REUSE>), dim3(blocks), dim3(kThreads), 0, st, a);
-            const hipError_t e = hipGetLastError();
+            const hipError_t e = launch(nz_ring_step<T, kRingIters, false, REUSE>, blocks, a, st);
             if (e != hipSuccess) return hip_failed(e, "ring reduce-scatter launch");
         }
     }
@@ -891,8 +899,7 @@ nz_status launch_ring_steps(RingArgs &a, u32 blocks, hipStream_t st, Collective 
         a.step = s;
         for (u64 c = 0; c < n_pieces; ++c) {
             a.g.win_off = c * (n_pieces > 1 ? a.g.win_len : 0);
-            hipLaunchKernelGGL((nz_ring_step<T, kRingIters, true, REUSE>), dim3(blocks), dim3(kThreads), 0, st, a);
-            const hipError_t e = hipGetLastError();
+            const hipError_t e = launch(nz_ring_step<T, kRingIters, true, REUSE>, blocks, a, st);
             if (e != hipSuccess) return hip_failed(e, "ring allgather launch");
         }
     }
@@ -910,8 +917,7 @@ nz_status launch_ring(RingArgs &a, u32 blocks, hipStream_t st, Collective what, 
 template <class T>
 nz_status launch_gather(const RingArgs &a, u32 blocks, hipStream_t st)
 {
-    hipLaunchKernelGGL((nz_gather_bcast<T, kRingIters>), dim3(blocks), dim3(kThreads), 0, st, a);
-    const hipError_t e = hipGetLastError();
+    const hipError_t e = launch(nz_gather_bcast<T, kRingIters>, blocks, a, st);
     return e == hipSuccess ? NZ_OK : hip_failed(e, "direct allgather launch");
 }
 
@@ -1007,11 +1013,8 @@ nz_status segment_copy(const void *const *src, void *const *dst, u32 n_nodes, co
         }
         bool aligned = true;
         for (u32 i = 0; i < r; ++i) aligned = aligned && ((a.src_off[i] - a.dst_off[i]) & 15) == 0;
-        if (aligned)
-            hipLaunchKernelGGL(nz_segment_copy<true>, dim3((u32)(blocks * n_nodes)), dim3(kThreads), 0, st, a);
-        else
-            hipLaunchKernelGGL(nz_segment_copy<false>, dim3((u32)(blocks * n_nodes)), dim3(kThreads), 0, st, a);
-        const hipError_t e = hipGetLastError();
+        const hipError_t e = aligned ? launch(nz_segment_copy<true>, (u32)(blocks * n_nodes), a, st)
+                                     : launch(nz_segment_copy<false>, (u32)(blocks * n_nodes), a, st);
         if (e != hipSuccess) return hip_failed(e, "segment copy launch");
     }
     return NZ_OK;

@@ -87,3 +87,11 @@ def test_failover_target_matches_oracle(orc):
                 nz.nz_failover_target(b, alive)
             continue
         assert nz.nz_failover_target(b, alive) == orc.failover_target(b, alive)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
