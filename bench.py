@@ -59,6 +59,9 @@ def parse_args():
                         "node) or the order a node sends its segments in (misaligned runs: LDS path)")
     p.add_argument("--graph", action="store_true",
                    help="capture one step in a HIP graph and time its replays (no per-part times)")
+    p.add_argument("--sweep", action="store_true",
+                   help="instead of the step: time fused and ring-stepwise allreduce over message sizes "
+                        "2 KB .. 64 MB (fp32, 2 rails 1:1) at 4 and 8 nodes and print one JSON line")
     p.add_argument("--cpu-sample-elems", type=int, default=8 * 1024 * 1024)
     return p.parse_args()
 
@@ -124,6 +127,49 @@ def cpu_baseline(w, n_sample: int, parts):
     }
 
 
+def size_sweep(torch, nz, dev) -> int:
+    """Latency and payload throughput (message bytes / time, the paper's definition) of one
+    allreduce per message size, the range of the paper's allreduce benchmark.  The fit
+    t = t0 + S / B per mode gives the fixed cost per call and the asymptotic payload rate,
+    the two quantities of the paper's network efficiency model (Sec. 2.1.2, Eq. 2)."""
+    rows = []
+    for N in (4, 8):
+        for log2 in range(11, 27):
+            S = 1 << log2
+            n = S // 4
+            ins = [torch.randn(n, device=dev) * 1e-2 for _ in range(N)]
+            outs = [torch.empty_like(t) for t in ins]
+            row = {"n_nodes": N, "msg_bytes": S}
+            for mode in ("fused", "ring-stepwise"):
+                reps = 200 if S <= (1 << 22) else 30
+                for _ in range(5):
+                    nz.nz_allreduce_sim(ins, n, (1, 1), "f32", mode, outs)
+                torch.cuda.synchronize()
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                for _ in range(reps):
+                    nz.nz_allreduce_sim(ins, n, (1, 1), "f32", mode, outs)
+                b.record()
+                torch.cuda.synchronize()
+                us = a.elapsed_time(b) * 1e3 / reps
+                row[mode] = {"us": round(us, 2), "payload_GBps": round(S / us / 1e3, 3)}
+            rows.append(row)
+    fits = {}
+    for N in (4, 8):
+        for mode in ("fused", "ring-stepwise"):
+            pts = [(r["msg_bytes"], r[mode]["us"]) for r in rows if r["n_nodes"] == N]
+            # least squares of t = t0 + S / B
+            m = len(pts)
+            sx = sum(x for x, _ in pts); sy = sum(y for _, y in pts)
+            sxx = sum(x * x for x, _ in pts); sxy = sum(x * y for x, y in pts)
+            slope = (m * sxy - sx * sy) / (m * sxx - sx * sx)
+            t0 = (sy - slope * sx) / m
+            fits[f"{mode}_N{N}"] = {"t0_us": round(t0, 2), "payload_GBps": round(1.0 / slope / 1e3, 2),
+                                    "half_efficiency_bytes": int(t0 / slope)}
+    print(json.dumps({"sweep": rows, "fit_t_equals_t0_plus_S_over_B": fits}), flush=True)
+    return 0
+
+
 def main() -> int:
     args = parse_args()
     if args.gpus != 1:
@@ -142,6 +188,8 @@ def main() -> int:
     nz.load()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+    if args.sweep:
+        return size_sweep(torch, nz, dev)
     w = inputs.WORKLOADS[args.workload]
     parts = [p for p in args.parts.split(",") if p]
     N, n, e = w.n_nodes, w.n_elems, inputs.ELEM_BYTES[w.dtype]
