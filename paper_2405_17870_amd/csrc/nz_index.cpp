@@ -82,6 +82,28 @@ nz_status nz_segment_map(const uint64_t *rail_off, uint32_t n_rails, uint32_t n_
     return nz::segment_map(rail_off, n_rails, n_nodes, seg_off);
 }
 
+// Sec. 4.4: the surviving rail that was allocated the most data takes over a
+// failed rail's slice.
+nz_status nz_failover_target(const uint64_t *rail_off, uint32_t n_rails, const uint8_t *alive,
+                             uint32_t *target)
+{
+    if (rail_off == nullptr || alive == nullptr || target == nullptr || n_rails == 0)
+        return NZ_ERR_INVALID_ARG;
+    bool found = false;
+    uint64_t most = 0;
+    for (uint32_t k = 0; k < n_rails; ++k) {
+        if (rail_off[k + 1] < rail_off[k]) return NZ_ERR_INVALID_ARG;
+        if (!alive[k]) continue;
+        const uint64_t len = rail_off[k + 1] - rail_off[k];
+        if (!found || len > most) {
+            found = true;
+            most = len;
+            *target = k;
+        }
+    }
+    return found ? NZ_OK : NZ_ERR_INVALID_ARG;
+}
+
 uint32_t nz_dtype_bytes(nz_dtype dtype)
 {
     switch (dtype) {

@@ -1190,26 +1190,6 @@ nz_status nz_allreduce_sim_chunked(const void *const *node_bufs, uint32_t n_node
                           chunk_elems == UINT64_MAX ? UINT64_MAX - 1 : chunk_elems);
 }
 
-nz_status nz_failover_target(const uint64_t *rail_off, uint32_t n_rails, const uint8_t *alive,
-                             uint32_t *target)
-{
-    if (rail_off == nullptr || alive == nullptr || target == nullptr || n_rails == 0)
-        return NZ_ERR_INVALID_ARG;
-    bool found = false;
-    u64 most = 0;
-    for (u32 k = 0; k < n_rails; ++k) {
-        if (rail_off[k + 1] < rail_off[k]) return NZ_ERR_INVALID_ARG;
-        if (!alive[k]) continue;
-        const u64 len = rail_off[k + 1] - rail_off[k];
-        if (!found || len > most) {
-            found = true;
-            most = len;
-            *target = k;
-        }
-    }
-    return found ? NZ_OK : NZ_ERR_INVALID_ARG;
-}
-
 nz_status nz_allreduce_sim_failover(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
                                     const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype,
                                     nz_mode mode, void *const *out_bufs, uint32_t failed_rail,
