@@ -66,15 +66,19 @@ def parse_args():
     return p.parse_args()
 
 
+def device_code_digest() -> str:
+    """SHA-256 over the device code the counters were taken on (csrc/nz_device.h)."""
+    src = os.path.join(ROOT, "paper_2405_17870_amd", "csrc", "nz_device.h")
+    return hashlib.sha256(open(src, "rb").read()).hexdigest()
+
+
 def recorded_traffic(kind: str):
-    """HBM bytes per launch from the committed counter runs, or None if the kernel source has
+    """HBM bytes per launch from the committed counter runs, or None if the kernels have
     changed since they were taken."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    src = os.path.join(ROOT, "paper_2405_17870_amd", "csrc", "nz_kernels.hip")
     try:
         rec = json.load(open(path))
-        digest = hashlib.sha256(open(src, "rb").read()).hexdigest()
-        if rec.get("kernel_source_sha256") != digest:
+        if rec.get("kernel_source_sha256") != device_code_digest():
             return None
         return rec.get(kind)
     except (OSError, ValueError):

@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libnezha_sim.so")
-SOURCES = [os.path.join(CSRC, "nz_kernels.hip"), os.path.join(CSRC, "nz_index.cpp"),
+SOURCES = [os.path.join(CSRC, "nz_host.hip"), os.path.join(CSRC, "nz_index.cpp"),
            os.path.join(CSRC, "nz_balance.cpp")]
 
 

@@ -1,6 +1,7 @@
-// HIP kernels (gfx950, wave64) and C-ABI entry points of the allreduce
-// reduction engine: fused N-way reduce + broadcast, ring reduce-scatter and
-// allgather steps, and the segment pack / unpack copy.
+// Device code of the allreduce reduction engine (gfx950, wave64): the fused
+// N-way reduce + broadcast, the ring reduce-scatter / allgather step, the
+// direct allgather and the segment copy, with the argument blocks they read.
+// Included by nz_host.hip only.
 //
 // Nezha (arXiv 2405.17870): the aggregation phase of the allreduce (Sec. 4.2),
 // run per rail on that rail's slice (Sec. 3.4, 4.1), with the ring schedule of
@@ -11,19 +12,18 @@
 // coalesced accesses on a 16-byte grid that is common to every buffer (all
 // bases are 256-byte aligned and all nodes use the same element offsets),
 // per-element handling of the few bytes where a segment boundary falls inside
-// a 16-byte vector, and LDS staging only in the copy kernel, the one place
-// where source and destination can be misaligned relative to each other.
+// a 16-byte vector, and a cross-lane exchange only in the copy kernel, the one
+// place where source and destination can be misaligned relative to each other.
 //
 // All per-call tables (node pointers, rail geometry, copy descriptors) travel
 // in the kernel-argument block: no device workspace, no allocation, no
 // host-to-device copy, and a call can be captured in a HIP graph as it is.
+#ifndef NZ_DEVICE_H
+#define NZ_DEVICE_H
+
 #include <hip/hip_runtime.h>
 
-#include <algorithm>
-#include <cstdio>
-#include <cstring>
-#include <utility>
-#include <vector>
+#include <cstdint>
 
 #include "nz_internal.h"
 
@@ -748,493 +748,6 @@ __global__ __launch_bounds__(kThreads) void nz_segment_copy(const CopyArgs)
     }
 }
 
-// ---------------------------------------------------------------------------
-// Host side
-// ---------------------------------------------------------------------------
-
-thread_local char g_hip_error[256] = "";
-
-nz_status hip_failed(hipError_t e, const char *what)
-{
-    std::snprintf(g_hip_error, sizeof g_hip_error, "%s: %s", what, hipGetErrorString(e));
-    return NZ_ERR_HIP;
-}
-
-// Launch a kernel whose only parameter is its argument struct and return the
-// launch's own status (hipGetLastError could hand back an older error that
-// some other code of the process left behind).
-template <class Args>
-hipError_t launch(void (*kernel)(const Args), u32 blocks, const Args &args, hipStream_t st)
-{
-    void *params[] = {const_cast<Args *>(&args)};
-    return hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3(blocks), dim3(kThreads), params, 0, st);
-}
-
-bool aligned256(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
-
-// Fill the geometry for tiles of tile_vecs 16-byte vectors.  Returns the
-// number of workgroups, or 0 if it does not fit the grid.
-constexpr u64 kNothingToDo = UINT64_MAX;  // every selected rail is empty
-
-u64 build_geometry(RailGeom &g, const u64 *rail_off, u32 n_rails, u32 n_nodes, u32 elem_shift,
-                   u32 tile_vecs, u32 rail_mask = 0xffffffffu, u64 piece_elems = UINT64_MAX)
-{
-    std::memset(&g, 0, sizeof g);
-    g.n_rails = n_rails;
-    g.n_nodes = n_nodes;
-    g.win_off = 0;
-    g.win_len = piece_elems;
-    u64 total = 0;
-    for (u32 k = 0; k < n_rails; ++k) {
-        // A rail left out of this launch keeps its place but has no elements.
-        const u64 len = (rail_mask >> k & 1u) ? rail_off[k + 1] - rail_off[k] : 0;
-        g.off[k] = rail_off[k];
-        g.q[k] = len / n_nodes;
-        g.rem[k] = (u32)(len % n_nodes);
-        u64 most = 0;
-        if (piece_elems != UINT64_MAX && len > 0) {
-            // Pieces start anywhere: bound the tiles a piece can touch.
-            const u64 longest = std::min<u64>(g.q[k] + (g.rem[k] ? 1 : 0), piece_elems);
-            const u64 vecs = ((longest << elem_shift) + 15) / 16 + 1;
-            most = longest ? (vecs + tile_vecs - 1) / tile_vecs + 1 : 0;
-        } else {
-            // Exact maximum, over the rail's segments, of the tiles a segment touches.
-            for (u32 j = 0; j < n_nodes && len > 0; ++j) {
-                const u64 beg = g.off[k] + j * g.q[k] + std::min<u64>(j, g.rem[k]);
-                const u64 sl = g.q[k] + (j < g.rem[k] ? 1 : 0);
-                if (sl == 0) continue;
-                const u64 v0 = (beg << elem_shift) >> 4;
-                const u64 v1 = (((beg + sl) << elem_shift) + 15) >> 4;
-                most = std::max<u64>(most, (v1 - 1) / tile_vecs - v0 / tile_vecs + 1);
-            }
-        }
-        if (most > 0xffffffffull) return 0;
-        g.tps[k] = (u32)most;
-        g.tile0[k] = (u32)total;
-        total += most * n_nodes;
-        if (total > 0x7fffffffull) return 0;
-    }
-    g.off[n_rails] = rail_off[n_rails];
-    g.tile0[n_rails] = (u32)total;
-    return total == 0 ? kNothingToDo : total;
-}
-
-struct PtrRef {
-    uintptr_t p;
-    bool written;
-};
-
-// Buffers of `bytes` bytes each: a written buffer may not partially overlap
-// any other buffer.
-bool partial_overlap(std::vector<PtrRef> &v, u64 bytes)
-{
-    std::sort(v.begin(), v.end(), [](const PtrRef &x, const PtrRef &y) { return x.p < y.p; });
-    // merge equal pointers
-    size_t w = 0;
-    for (size_t i = 0; i < v.size(); ++i) {
-        if (w > 0 && v[w - 1].p == v[i].p)
-            v[w - 1].written = v[w - 1].written || v[i].written;
-        else
-            v[w++] = v[i];
-    }
-    v.resize(w);
-    for (size_t i = 0; i + 1 < v.size(); ++i)
-        if (v[i + 1].p - v[i].p < bytes && (v[i].written || v[i + 1].written)) return true;
-    return false;
-}
-
-struct Range {
-    uintptr_t lo, hi;
-    bool written;
-};
-
-// True if a written range overlaps any other range (read ranges may overlap
-// each other freely).
-bool written_range_overlaps(std::vector<Range> &v)
-{
-    std::sort(v.begin(), v.end(), [](const Range &x, const Range &y) { return x.lo < y.lo; });
-    uintptr_t end_any = 0, end_written = 0;
-    for (const Range &r : v) {
-        if (r.lo == r.hi) continue;
-        if (r.written ? r.lo < end_any : r.lo < end_written) return true;
-        end_any = std::max(end_any, r.hi);
-        if (r.written) end_written = std::max(end_written, r.hi);
-    }
-    return false;
-}
-
-template <class T>
-nz_status launch_fused(const FusedArgs &a, u32 blocks, hipStream_t st)
-{
-    const hipError_t e = launch(nz_fused_reduce_bcast<T>, blocks, a, st);
-    return e == hipSuccess ? NZ_OK : hip_failed(e, "fused reduce launch");
-}
-
-#ifndef NZ_RING_ITERS
-#define NZ_RING_ITERS 2
-#endif
-constexpr int kRingIters = NZ_RING_ITERS;
-
-enum Collective { kAllreduce, kReduceScatter, kAllgather };
-
-// n_pieces > 1: every step is issued as n_pieces launches, piece c of every
-// segment before piece c + 1 (a.g.win_len elements each).
-// Bytes of one ring step up to which the step's output is kept in cache for
-// the next step to read (half of the 256 MB last-level cache).
-constexpr u64 kRingReuseBytes = 128ull << 20;
-
-template <class T, bool REUSE>
-nz_status launch_ring_steps(RingArgs &a, u32 blocks, hipStream_t st, Collective what, u64 n_pieces)
-{
-    const u32 N = a.g.n_nodes;
-    for (u32 s = 0; s + 1 < N && what != kAllgather; ++s) {
-        a.step = s;
-        for (u64 c = 0; c < n_pieces; ++c) {
-            a.g.win_off = c * (n_pieces > 1 ? a.g.win_len : 0);
-            const hipError_t e = launch(nz_ring_step<T, kRingIters, false, REUSE>, blocks, a, st);
-            if (e != hipSuccess) return hip_failed(e, "ring reduce-scatter launch");
-        }
-    }
-    for (u32 s = 0; s + 1 < N && what != kReduceScatter; ++s) {
-        a.step = s;
-        for (u64 c = 0; c < n_pieces; ++c) {
-            a.g.win_off = c * (n_pieces > 1 ? a.g.win_len : 0);
-            const hipError_t e = launch(nz_ring_step<T, kRingIters, true, REUSE>, blocks, a, st);
-            if (e != hipSuccess) return hip_failed(e, "ring allgather launch");
-        }
-    }
-    return NZ_OK;
-}
-
-template <class T>
-nz_status launch_ring(RingArgs &a, u32 blocks, hipStream_t st, Collective what, u64 n_pieces)
-{
-    const u64 step_bytes = (a.g.off[a.g.n_rails] - a.g.off[0]) << a.elem_shift;
-    return step_bytes <= kRingReuseBytes ? launch_ring_steps<T, true>(a, blocks, st, what, n_pieces)
-                                         : launch_ring_steps<T, false>(a, blocks, st, what, n_pieces);
-}
-
-template <class T>
-nz_status launch_gather(const RingArgs &a, u32 blocks, hipStream_t st)
-{
-    const hipError_t e = launch(nz_gather_bcast<T, kRingIters>, blocks, a, st);
-    return e == hipSuccess ? NZ_OK : hip_failed(e, "direct allgather launch");
-}
-
-nz_status segment_copy(const void *const *src, void *const *dst, u32 n_nodes, const u64 *seg_off,
-                       u32 n_rails, u32 rail, const u32 *seg_ids, u32 n_segs, u32 elem_bytes,
-                       bool packing, u64 capacity, u64 *packed_bytes, hipStream_t st)
-{
-    if (src == nullptr || dst == nullptr || seg_off == nullptr) return NZ_ERR_INVALID_ARG;
-    if (n_nodes == 0 || n_rails == 0 || rail >= n_rails) return NZ_ERR_INVALID_ARG;
-    if (n_segs > 0 && seg_ids == nullptr) return NZ_ERR_INVALID_ARG;
-    if (elem_bytes != 2 && elem_bytes != 4) return NZ_ERR_INVALID_ARG;
-    if (n_nodes > NZ_MAX_NODES || n_rails > NZ_MAX_RAILS || n_segs > NZ_MAX_NODES)
-        return NZ_ERR_UNSUPPORTED;
-    const u64 *row = seg_off + (size_t)rail * (n_nodes + 1);
-    for (u32 j = 0; j < n_nodes; ++j)
-        if (row[j + 1] < row[j] || row[j + 1] > (UINT64_MAX >> 3)) return NZ_ERR_INVALID_ARG;
-    std::vector<bool> seen(n_nodes, false);
-    u64 total = 0;
-    for (u32 i = 0; i < n_segs; ++i) {
-        if (seg_ids[i] >= n_nodes) return NZ_ERR_INVALID_ARG;
-        if (!packing) {
-            if (seen[seg_ids[i]]) return NZ_ERR_INVALID_ARG;
-            seen[seg_ids[i]] = true;
-        }
-        total += (row[seg_ids[i] + 1] - row[seg_ids[i]]) * elem_bytes;
-    }
-    if (packing && total > capacity) return NZ_ERR_CAPACITY;
-    const u64 node_span_lo = row[0] * elem_bytes, node_span_hi = row[n_nodes] * elem_bytes;
-    for (u32 m = 0; m < n_nodes; ++m) {
-        if (src[m] == nullptr || dst[m] == nullptr) return NZ_ERR_INVALID_ARG;
-        if (!aligned256(src[m]) || !aligned256(dst[m])) return NZ_ERR_ALIGNMENT;
-    }
-    // A written range may not overlap any other range.  The packed side of
-    // buffer m is [base, base + total), the node side is the rail's span.
-    {
-        std::vector<Range> ranges;
-        ranges.reserve(2 * n_nodes);
-        for (u32 m = 0; m < n_nodes && total > 0; ++m) {
-            const uintptr_t s0 = reinterpret_cast<uintptr_t>(src[m]), d0 = reinterpret_cast<uintptr_t>(dst[m]);
-            if (packing) {
-                ranges.push_back({s0 + node_span_lo, s0 + node_span_hi, false});
-                ranges.push_back({d0, d0 + total, true});
-            } else {
-                ranges.push_back({s0, s0 + total, false});
-                ranges.push_back({d0 + node_span_lo, d0 + node_span_hi, true});
-            }
-        }
-        if (written_range_overlaps(ranges)) return NZ_ERR_UNSUPPORTED;
-    }
-    if (packed_bytes) *packed_bytes = total;
-    if (total == 0) return NZ_OK;
-
-    // Runs: consecutive list entries that are also consecutive in the node
-    // buffer merge into one (a whole rail in order is a single run).
-    struct Run { u64 node_off, pack_off, len; };
-    std::vector<Run> runs;
-    u64 pos = 0;
-    for (u32 i = 0; i < n_segs; ++i) {
-        const u64 off = row[seg_ids[i]] * elem_bytes;
-        const u64 len = (row[seg_ids[i] + 1] - row[seg_ids[i]]) * elem_bytes;
-        if (len == 0) continue;
-        if (!runs.empty() && runs.back().node_off + runs.back().len == off)
-            runs.back().len += len;
-        else
-            runs.push_back({off, pos, len});
-        pos += len;
-    }
-
-    constexpr u64 TILE = (u64)kCopyIters * kThreads;
-    size_t next = 0;
-    while (next < runs.size()) {
-        CopyArgs a;
-        std::memset(&a, 0, sizeof a);
-        a.elem_bytes = elem_bytes;
-        u64 blocks = 0;
-        u32 r = 0;
-        for (; r < (u32)kCopyMaxRuns && next < runs.size(); ++r, ++next) {
-            const Run &run = runs[next];
-            a.src_off[r] = packing ? run.node_off : run.pack_off;
-            a.dst_off[r] = packing ? run.pack_off : run.node_off;
-            a.len[r] = run.len;
-            a.tile0[r] = (u32)blocks;
-            const u64 v0 = a.dst_off[r] >> 4, v1 = (a.dst_off[r] + run.len + 15) >> 4;
-            blocks += (v1 - 1) / TILE - v0 / TILE + 1;
-            if (blocks * n_nodes > 0x7fffffffull) return NZ_ERR_UNSUPPORTED;
-        }
-        a.tile0[r] = (u32)blocks;
-        a.n_runs = r;
-        a.n_nodes = n_nodes;
-        for (u32 m = 0; m < n_nodes; ++m) {
-            a.src[m] = src[m];
-            a.dst[m] = dst[m];
-        }
-        bool aligned = true;
-        for (u32 i = 0; i < r; ++i) aligned = aligned && ((a.src_off[i] - a.dst_off[i]) & 15) == 0;
-        const hipError_t e = aligned ? launch(nz_segment_copy<true>, (u32)(blocks * n_nodes), a, st)
-                                     : launch(nz_segment_copy<false>, (u32)(blocks * n_nodes), a, st);
-        if (e != hipSuccess) return hip_failed(e, "segment copy launch");
-    }
-    return NZ_OK;
-}
-
-// Common host side of the three collectives.  For kAllgather node_bufs and
-// out_bufs are the same array: the operation is in place.
-// rail_mask selects the rails a call works on (bit k = rail k); piece_elems is
-// the Ring_Chunked piece length (UINT64_MAX: whole segments).
-nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
-                         const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype, nz_mode mode,
-                         void *const *out_bufs, hipStream_t st, u32 rail_mask = 0xffffffffu,
-                         u64 piece_elems = UINT64_MAX)
-{
-    if (node_bufs == nullptr || out_bufs == nullptr || ratios == nullptr) return NZ_ERR_INVALID_ARG;
-    if (n_nodes == 0 || n_rails == 0) return NZ_ERR_INVALID_ARG;
-    const u32 eb = nz_dtype_bytes(dtype);
-    if (eb == 0) return NZ_ERR_INVALID_ARG;
-    if (mode != NZ_RING_STEPWISE && mode != NZ_FUSED) return NZ_ERR_INVALID_ARG;
-    if (n_nodes > NZ_MAX_NODES || n_rails > NZ_MAX_RAILS) return NZ_ERR_UNSUPPORTED;
-
-    u64 rail_off[NZ_MAX_RAILS + 1];
-    const nz_status ps = nz::rail_partition(n_elems, eb, NZ_RAIL_ALIGN_BYTES, ratios, n_rails, rail_off);
-    if (ps != NZ_OK) return ps;
-
-    for (u32 i = 0; i < n_nodes; ++i) {
-        if (node_bufs[i] == nullptr || out_bufs[i] == nullptr) return NZ_ERR_INVALID_ARG;
-        if (!aligned256(node_bufs[i]) || !aligned256(out_bufs[i])) return NZ_ERR_ALIGNMENT;
-    }
-    const u64 bytes = n_elems * eb;
-    {
-        std::vector<PtrRef> refs;
-        refs.reserve(2 * n_nodes);
-        for (u32 i = 0; i < n_nodes; ++i) {
-            refs.push_back({reinterpret_cast<uintptr_t>(node_bufs[i]), false});
-            refs.push_back({reinterpret_cast<uintptr_t>(out_bufs[i]), true});
-        }
-        if (partial_overlap(refs, bytes)) return NZ_ERR_UNSUPPORTED;
-    }
-    if (mode == NZ_RING_STEPWISE || what != kAllreduce) {
-        // Outputs pairwise distinct; an output may alias only its own node's input.
-        std::vector<std::pair<uintptr_t, u32>> ins, outs;
-        for (u32 i = 0; i < n_nodes; ++i) {
-            ins.push_back({reinterpret_cast<uintptr_t>(node_bufs[i]), i});
-            outs.push_back({reinterpret_cast<uintptr_t>(out_bufs[i]), i});
-        }
-        std::sort(ins.begin(), ins.end());
-        std::sort(outs.begin(), outs.end());
-        for (u32 i = 0; i + 1 < n_nodes; ++i)
-            if (outs[i].first == outs[i + 1].first) return NZ_ERR_UNSUPPORTED;
-        for (u32 i = 0; i < n_nodes; ++i) {
-            auto it = std::lower_bound(ins.begin(), ins.end(), std::make_pair(outs[i].first, 0u));
-            for (; it != ins.end() && it->first == outs[i].first; ++it)
-                if (it->second != outs[i].second) return NZ_ERR_UNSUPPORTED;
-        }
-    }
-    if (n_elems == 0) return NZ_OK;
-
-    const u32 shift = (eb == 4) ? 2 : 1;
-
-    if (mode == NZ_FUSED && what == kAllgather) {
-        RingArgs a;
-        const u64 blocks =
-            build_geometry(a.g, rail_off, n_rails, n_nodes, shift, (u32)kRingIters * kThreads, rail_mask);
-        if (blocks == 0) return NZ_ERR_UNSUPPORTED;
-        if (blocks == kNothingToDo) return NZ_OK;
-        a.elem_shift = shift;
-        a.step = 0;
-        for (u32 i = 0; i < n_nodes; ++i) {
-            a.in[i] = out_bufs[i];
-            a.out[i] = out_bufs[i];
-        }
-        if (n_nodes == 1) return NZ_OK;
-        return eb == 4 ? launch_gather<TI32>(a, (u32)blocks, st) : launch_gather<TBF16>(a, (u32)blocks, st);
-    }
-
-    if (mode == NZ_FUSED) {
-        FusedArgs a;
-        u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, kThreads, rail_mask);
-        if (blocks == 0) return NZ_ERR_UNSUPPORTED;
-        if (blocks == kNothingToDo) return NZ_OK;
-        blocks += (u64)n_rails * n_nodes;  // the workgroups for segment edges
-        a.owner_only = (what == kReduceScatter) ? 1u : 0u;
-        a.n_out = 0;
-        for (u32 i = 0; i < n_nodes; ++i) {
-            a.in[i] = node_bufs[i];
-            bool dup = false;
-            for (u32 o = 0; o < a.n_out && !a.owner_only; ++o) dup = dup || (a.out[o] == out_bufs[i]);
-            if (!dup) a.out[a.n_out++] = out_bufs[i];
-        }
-        switch (dtype) {
-        case NZ_F32: return launch_fused<TF32>(a, (u32)blocks, st);
-        case NZ_I32: return launch_fused<TI32>(a, (u32)blocks, st);
-        case NZ_BF16: return launch_fused<TBF16>(a, (u32)blocks, st);
-        case NZ_F16: return launch_fused<TF16>(a, (u32)blocks, st);
-        }
-        return NZ_ERR_INVALID_ARG;
-    }
-
-    RingArgs a;
-    const u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, (u32)kRingIters * kThreads,
-                                      rail_mask, piece_elems);
-    if (blocks == 0) return NZ_ERR_UNSUPPORTED;
-    if (blocks == kNothingToDo) return NZ_OK;
-    u64 n_pieces = 1;
-    if (piece_elems != UINT64_MAX) {
-        u64 longest = 0;
-        for (u32 k = 0; k < n_rails; ++k) longest = std::max<u64>(longest, a.g.q[k] + (a.g.rem[k] ? 1 : 0));
-        n_pieces = std::max<u64>((longest + piece_elems - 1) / piece_elems, 1);
-        if (n_pieces > 1u << 20) return NZ_ERR_UNSUPPORTED;  // more launches than anybody means
-        if (n_pieces == 1) a.g.win_len = UINT64_MAX;
-    }
-    a.elem_shift = shift;
-    a.step = 0;
-    for (u32 i = 0; i < n_nodes; ++i) {
-        a.in[i] = node_bufs[i];
-        a.out[i] = out_bufs[i];
-    }
-    if (n_nodes == 1) {
-        // A ring of one node has no steps: the result is the node's own data.
-        if (what != kAllgather && out_bufs[0] != node_bufs[0]) {
-            const hipError_t e = hipMemcpyAsync(out_bufs[0], node_bufs[0], bytes, hipMemcpyDeviceToDevice, st);
-            if (e != hipSuccess) return hip_failed(e, "single-node copy");
-        }
-        return NZ_OK;
-    }
-    switch (dtype) {
-    case NZ_F32: return launch_ring<TF32>(a, (u32)blocks, st, what, n_pieces);
-    case NZ_I32: return launch_ring<TI32>(a, (u32)blocks, st, what, n_pieces);
-    case NZ_BF16: return launch_ring<TBF16>(a, (u32)blocks, st, what, n_pieces);
-    case NZ_F16: return launch_ring<TF16>(a, (u32)blocks, st, what, n_pieces);
-    }
-    return NZ_ERR_INVALID_ARG;
-}
-
-
 }  // namespace
 
-extern "C" {
-
-const char *nz_last_hip_error(void) { return g_hip_error; }
-
-nz_status nz_allreduce_sim(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
-                           const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype, nz_mode mode,
-                           void *const *out_bufs, void *stream)
-{
-    return run_collective(kAllreduce, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype, mode, out_bufs,
-                          static_cast<hipStream_t>(stream));
-}
-
-nz_status nz_reduce_scatter_sim(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
-                                const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype, nz_mode mode,
-                                void *const *out_bufs, void *stream)
-{
-    return run_collective(kReduceScatter, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype, mode,
-                          out_bufs, static_cast<hipStream_t>(stream));
-}
-
-nz_status nz_allgather_sim(void *const *bufs, uint32_t n_nodes, uint64_t n_elems, const uint32_t *ratios,
-                           uint32_t n_rails, nz_dtype dtype, nz_mode mode, void *stream)
-{
-    return run_collective(kAllgather, reinterpret_cast<const void *const *>(bufs), n_nodes, n_elems, ratios,
-                          n_rails, dtype, mode, bufs, static_cast<hipStream_t>(stream));
-}
-
-nz_status nz_allreduce_sim_chunked(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
-                                   const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype,
-                                   uint64_t chunk_elems, void *const *out_bufs, void *stream)
-{
-    if (chunk_elems == 0) return NZ_ERR_INVALID_ARG;
-    return run_collective(kAllreduce, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype, NZ_RING_STEPWISE,
-                          out_bufs, static_cast<hipStream_t>(stream), 0xffffffffu,
-                          chunk_elems == UINT64_MAX ? UINT64_MAX - 1 : chunk_elems);
-}
-
-nz_status nz_allreduce_sim_failover(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
-                                    const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype,
-                                    nz_mode mode, void *const *out_bufs, uint32_t failed_rail,
-                                    uint32_t *takeover_rail, void *stream)
-{
-    if (ratios == nullptr || n_rails == 0 || failed_rail >= n_rails) return NZ_ERR_INVALID_ARG;
-    if (n_rails > NZ_MAX_RAILS) return NZ_ERR_UNSUPPORTED;
-    const u32 eb = nz_dtype_bytes(dtype);
-    if (eb == 0) return NZ_ERR_INVALID_ARG;
-    u64 rail_off[NZ_MAX_RAILS + 1];
-    const nz_status ps = nz::rail_partition(n_elems, eb, NZ_RAIL_ALIGN_BYTES, ratios, n_rails, rail_off);
-    if (ps != NZ_OK) return ps;
-    uint8_t alive[NZ_MAX_RAILS];
-    for (u32 k = 0; k < n_rails; ++k) alive[k] = (k != failed_rail);
-    u32 target = 0;
-    const nz_status ts = nz_failover_target(rail_off, n_rails, alive, &target);
-    if (ts != NZ_OK) return ts;  // no rail survives
-    if (takeover_rail) *takeover_rail = target;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    // First the surviving rails' own slices, then -- on the same stream, as the
-    // take-over rail's next task -- the failed rail's slice, still cut as it was.
-    const u32 all = (n_rails >= 32) ? 0xffffffffu : ((1u << n_rails) - 1u);
-    const nz_status first = run_collective(kAllreduce, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype,
-                                           mode, out_bufs, st, all & ~(1u << failed_rail));
-    if (first != NZ_OK) return first;
-    return run_collective(kAllreduce, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype, mode, out_bufs, st,
-                          1u << failed_rail);
-}
-
-nz_status nz_pack(const void *const *node_bufs, uint32_t n_nodes, const uint64_t *seg_off,
-                  uint32_t n_rails, uint32_t rail, const uint32_t *seg_ids, uint32_t n_segs,
-                  uint32_t elem_bytes, void *const *send_bufs, uint64_t send_capacity_bytes,
-                  uint64_t *packed_bytes, void *stream)
-{
-    return segment_copy(node_bufs, send_bufs, n_nodes, seg_off, n_rails, rail, seg_ids, n_segs,
-                        elem_bytes, true, send_capacity_bytes, packed_bytes,
-                        static_cast<hipStream_t>(stream));
-}
-
-nz_status nz_unpack(const void *const *send_bufs, uint32_t n_nodes, const uint64_t *seg_off,
-                    uint32_t n_rails, uint32_t rail, const uint32_t *seg_ids, uint32_t n_segs,
-                    uint32_t elem_bytes, void *const *node_bufs, void *stream)
-{
-    return segment_copy(send_bufs, node_bufs, n_nodes, seg_off, n_rails, rail, seg_ids, n_segs,
-                        elem_bytes, false, 0, nullptr, static_cast<hipStream_t>(stream));
-}
-
-}  // extern "C"
+#endif  // NZ_DEVICE_H
