@@ -56,7 +56,7 @@ def parse_args():
                    help="piece length of the optional part 'chunked' (Ring_Chunked)")
     p.add_argument("--pack-order", default="rail", choices=["rail", "ring"],
                    help="segment list of pack/unpack: the whole rail in order (one aligned run per "
-                        "node) or the order a node sends its segments in (misaligned runs: LDS path)")
+                        "node) or the order a node sends its segments in (misaligned runs: the re-alignment path)")
     p.add_argument("--graph", action="store_true",
                    help="capture one step in a HIP graph and time its replays (no per-part times)")
     p.add_argument("--sweep", action="store_true",
