@@ -33,6 +33,7 @@ class HbmArena:
     """One big device allocation with a bump pointer per 96 GiB region."""
 
     def __init__(self, device="cuda:0", reserve_bytes: int = 5 * GIB):
+        torch.cuda.empty_cache()          # hand cached blocks back so the arena can be one allocation
         free, total = torch.cuda.mem_get_info(device)
         size = min(free - reserve_bytes, N_REGIONS * REGION_BYTES - reserve_bytes)
         size = (size // ALIGN) * ALIGN

@@ -11,6 +11,7 @@ import torch
 
 from paper_2405_17870_amd import inputs
 from paper_2405_17870_amd import nezha_sim as nz
+from paper_2405_17870_amd import placement
 
 import gpu_util as gu
 
@@ -80,9 +81,21 @@ def test_c4_sampled_ranges_and_packed_route(orc):
     w = inputs.WORKLOADS["c4"]
     N, n = w.n_nodes, w.n_elems
     _say("c4: generating 32 x 335M bf16")
-    ins = inputs.workload_buffers(w, device=gu.DEV)
-    _say("c4: fused")
-    outs = _run(w, "fused", ins)
+    # buffers placed as the benchmark places them (inputs in the first HBM region, outputs striped)
+    torch.cuda.empty_cache()
+    arena = placement.try_arena(gu.DEV)
+    if arena is not None:
+        ins = [arena.alloc(n, torch.bfloat16, 0) for _ in range(N)]
+        for i in range(N):
+            ins[i].copy_(inputs.node_buffer(w.dtype, n, w.seed, i, device=gu.DEV, std=w.std))
+        outs = arena.alloc_striped(N, n, torch.bfloat16)
+        _say("c4: fused (arena placement)")
+        nz.nz_allreduce_sim(ins, n, w.ratios, w.dtype, "fused", outs)
+        torch.cuda.synchronize()
+    else:
+        ins = inputs.workload_buffers(w, device=gu.DEV)
+        _say("c4: fused (plain allocations)")
+        outs = _run(w, "fused", ins)
     assert _all_equal(outs)
     rng = np.random.default_rng(4)
     escapes = 0
@@ -97,11 +110,17 @@ def test_c4_sampled_ranges_and_packed_route(orc):
     _say("c4: packed route")
     b = nz.nz_rail_partition(n, 2, w.ratios)
     seg = nz.nz_segment_map(b, N)
-    routed = [torch.zeros_like(t) for t in ins]
+    if arena is not None:
+        routed = arena.alloc_striped(N, n, torch.bfloat16, start=1)
+        for t in routed:
+            t.zero_()
+    else:
+        routed = [torch.zeros_like(t) for t in ins]
     ids = list(range(N))
     for rail in range(len(w.ratios)):
         L = int(b[rail + 1] - b[rail])
-        send = [torch.empty(L, dtype=torch.bfloat16, device=gu.DEV) for _ in range(N)]
+        send = (arena.alloc_striped(N, L, torch.bfloat16, start=2) if arena is not None
+                else [torch.empty(L, dtype=torch.bfloat16, device=gu.DEV) for _ in range(N)])
         assert nz.nz_pack(ins, seg, rail, ids, 2, send, L * 2) == L * 2
         nz.nz_allreduce_sim(send, L, (1,), "bf16", "fused", send)
         nz.nz_unpack(send, seg, rail, ids, 2, routed)
