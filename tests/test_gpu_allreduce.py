@@ -28,7 +28,18 @@ SHAPES = [
     (8, (100, 40), 70_001), (8, (100, 100, 40), 12_345), (5, (7, 0, 3), 4_097),
     (32, (100, 25), 100_003), (128, (100, 100, 40, 10), 33_333), (128, (1, 1), 100),
     (7, (1, 1, 1, 1, 1, 1, 1, 1), 9_999), (9, (5,), 300_000), (17, (2, 5), 262_144 + 17),
+    # segments of exactly 1, 63, 64, 65 elements; fewer elements than nodes (empty segments)
+    (4, (1,), 4), (4, (1,), 4 * 63), (4, (1,), 4 * 64), (4, (1,), 4 * 65), (8, (1,), 5), (8, (3, 1), 130),
+    # segment length 1001 = 1 mod 8: the 8 segment starts fall in every alignment class of a
+    # 16-byte vector (0, 2, .. 14 bytes for 2-byte elements; 0, 4, 8, 12 for 4-byte elements)
+    (8, (1,), 8 * 1001),
 ]
+
+
+def test_shapes_cover_every_alignment_class(orc):
+    for e in (2, 4):
+        seg = orc.segment_map(orc.rail_partition(8 * 1001, (1,), e), 8)
+        assert {int(x) * e % 16 for x in seg[0, :8]} == set(range(0, 16, e))
 
 
 @pytest.mark.parametrize("dtype", ["f32", "i32", "bf16", "f16"])

@@ -58,7 +58,8 @@ def _case(orc, N, ratios, n, e, rail, ids, capacity_slack=64):
 @pytest.mark.parametrize("e", [2, 4])
 def test_pack_unpack_whole_rail_and_ring_order(orc, e):
     for N, ratios, n in [(3, (3, 1), 200), (8, (100, 40), 70_001), (8, (100, 100, 40), 123_457),
-                         (32, (100, 25), 400_003), (128, (100, 100, 40, 10), 300_007), (1, (1,), 5000)]:
+                         (32, (100, 25), 400_003), (128, (100, 100, 40, 10), 300_007), (1, (1,), 5000),
+                         (8, (1,), 8 * 1001), (4, (1,), 4 * 63), (8, (1,), 5)]:
         R = len(ratios)
         for rail in range(R):
             _case(orc, N, ratios, n, e, rail, list(range(N)))                       # whole rail
