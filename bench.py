@@ -35,8 +35,8 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E peak
 def parse_args():
     p = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     p.add_argument("--gpus", type=int, default=1)
-    p.add_argument("--steps", type=int, default=10)
-    p.add_argument("--warmup", type=int, default=2)
+    p.add_argument("--steps", type=int, default=20)
+    p.add_argument("--warmup", type=int, default=5)
     p.add_argument("--workload", default="c4", help="c1, c1_i32, c2, c3, c4 (default), c5")
     p.add_argument("--parts", default="fused,ring,pack,unpack",
                    help="comma list of parts to run in a step (default: all four); also available: "
@@ -62,7 +62,7 @@ def parse_args():
     p.add_argument("--sweep", action="store_true",
                    help="instead of the step: time fused and ring-stepwise allreduce over message sizes "
                         "2 KB .. 64 MB (fp32, 2 rails 1:1) at 4 and 8 nodes and print one JSON line")
-    p.add_argument("--cpu-sample-elems", type=int, default=8 * 1024 * 1024)
+    p.add_argument("--cpu-sample-elems", type=int, default=32 * 1024 * 1024)
     return p.parse_args()
 
 
