@@ -11,7 +11,9 @@
  * Conventions for every entry point
  *   - Return value: nz_status.  Nothing is thrown, the process is never
  *     aborted.  All validation happens before any GPU work is enqueued: on a
- *     status other than NZ_OK nothing was launched and no output was written.
+ *     status other than NZ_OK nothing was launched and no output was written
+ *     (NZ_ERR_HIP excepted: a launch the runtime refuses may follow launches
+ *     of the same call that were accepted).
  *   - "host" pointers are ordinary process memory, read (or written) before
  *     the call returns; the caller may free them immediately afterwards.
  *   - "device" pointers are HIP device memory owned by the caller.  The

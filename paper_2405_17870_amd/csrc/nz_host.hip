@@ -17,10 +17,6 @@
 
 namespace {
 
-// ---------------------------------------------------------------------------
-// Host side
-// ---------------------------------------------------------------------------
-
 thread_local char g_hip_error[256] = "";
 
 nz_status hip_failed(hipError_t e, const char *what)
@@ -41,10 +37,13 @@ hipError_t launch(void (*kernel)(const Args), u32 blocks, const Args &args, hipS
 
 bool aligned256(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
 
-// Fill the geometry for tiles of tile_vecs 16-byte vectors.  Returns the
-// number of workgroups, or 0 if it does not fit the grid.
 constexpr u64 kNothingToDo = UINT64_MAX;  // every selected rail is empty
 
+// Fill the geometry for tiles of tile_vecs 16-byte vectors.  rail_mask selects
+// the rails that take part (bit k = rail k); piece_elems < UINT64_MAX makes the
+// launch work on pieces of that many elements of every segment.  Returns the
+// number of workgroups, kNothingToDo if there is no element to work on, or 0 if
+// the work does not fit a grid.
 u64 build_geometry(RailGeom &g, const u64 *rail_off, u32 n_rails, u32 n_nodes, u32 elem_shift,
                    u32 tile_vecs, u32 rail_mask = 0xffffffffu, u64 piece_elems = UINT64_MAX)
 {
@@ -146,12 +145,14 @@ constexpr int kRingIters = NZ_RING_ITERS;
 
 enum Collective { kAllreduce, kReduceScatter, kAllgather };
 
-// n_pieces > 1: every step is issued as n_pieces launches, piece c of every
-// segment before piece c + 1 (a.g.win_len elements each).
 // Bytes of one ring step up to which the step's output is kept in cache for
 // the next step to read (half of the 256 MB last-level cache).
 constexpr u64 kRingReuseBytes = 128ull << 20;
 
+// The launches of a ring: N - 1 reduce-scatter steps, then N - 1 allgather
+// steps (one half only for the phase collectives).  n_pieces > 1: every step
+// is issued as n_pieces launches, piece c of every segment before piece c + 1
+// (a.g.win_len elements each).
 template <class T, bool REUSE>
 nz_status launch_ring_steps(RingArgs &a, u32 blocks, hipStream_t st, Collective what, u64 n_pieces)
 {
@@ -418,7 +419,6 @@ nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t
     }
     return NZ_ERR_INVALID_ARG;
 }
-
 
 }  // namespace
 
