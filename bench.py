@@ -54,6 +54,8 @@ def parse_args():
                    help="with --placement packed: arena offset at which the buffers start")
     p.add_argument("--chunk-elems", type=int, default=1 << 20,
                    help="piece length of the optional part 'chunked' (Ring_Chunked)")
+    p.add_argument("--shared-output", action="store_true",
+                   help="fused part: every node's output is the same buffer (K = 1 distinct output)")
     p.add_argument("--pack-order", default="rail", choices=["rail", "ring"],
                    help="segment list of pack/unpack: the whole rail in order (one aligned run per "
                         "node) or the order a node sends its segments in (misaligned runs: the re-alignment path)")
@@ -235,7 +237,9 @@ def main() -> int:
     ids = list(range(N)) if args.pack_order == "rail" else [(N // 2 - s) % N for s in range(N)]
     torch.cuda.synchronize()
 
-    alg_bytes = {"fused": 2 * N * S, "ring": 5 * (N - 1) * S, "pack": 2 * N * S, "unpack": 2 * N * S,
+    fused_outs = [outs[1]] * N if args.shared_output else outs
+    K = 1 if args.shared_output else N
+    alg_bytes = {"fused": (N + K) * S, "ring": 5 * (N - 1) * S, "pack": 2 * N * S, "unpack": 2 * N * S,
                  # optional parts: the two halves on their own, fused form
                  "rs": (N + 1) * S, "ag": N * S,
                  # Ring_Chunked moves the ring's bytes in more launches; failover the fused bytes in two
@@ -243,7 +247,7 @@ def main() -> int:
 
     def run_part(p):
         if p == "fused":
-            nz.nz_allreduce_sim(ins, n, w.ratios, w.dtype, "fused", outs)
+            nz.nz_allreduce_sim(ins, n, w.ratios, w.dtype, "fused", fused_outs)
         elif p == "ring":
             nz.nz_allreduce_sim(ins, n, w.ratios, w.dtype, "ring-stepwise", outs)
         elif p == "rs":
@@ -338,7 +342,7 @@ def main() -> int:
         "config": {"workload": f"{w.name}: {N} simulated nodes x {n} {w.dtype} elements, "
                                f"rails {':'.join(map(str, w.ratios))}",
                    "storage_dtype": w.dtype, "n_nodes": N, "n_elems": n, "ratios": list(w.ratios),
-                   "parts": parts, "distinct_outputs": N, "placement": placement_note,
+                   "parts": parts, "distinct_outputs": K, "placement": placement_note,
                    "hip_graph": bool(args.graph)},
         "pct_of_hbm_peak": round(100.0 * step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
         "parts": part_stats,
