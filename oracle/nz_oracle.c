@@ -277,6 +277,42 @@ static void add_into(int dtype, void *dst, const void *src, uint64_t off, uint64
     }
 }
 
+/* The N-1 reduce-scatter steps (receive-and-add) over every rail. */
+static void ring_reduce_scatter(int dtype, int e, void *const *buf, uint32_t N,
+                                const uint64_t *seg, uint32_t n_rails, uint64_t *sent_bytes)
+{
+    for (uint32_t s = 0; s + 1 < N; ++s) {
+        for (uint32_t k = 0; k < n_rails; ++k) {
+            const uint64_t *row = seg + (size_t)k * (N + 1);
+            for (uint32_t r = 0; r < N; ++r) {
+                uint32_t j = (r + N - s) % N;
+                uint32_t d = (r + 1) % N;
+                uint64_t off = row[j], len = row[j + 1] - row[j];
+                add_into(dtype, buf[d], buf[r], off, len);
+                if (sent_bytes) sent_bytes[r] += len * (uint64_t)e;
+            }
+        }
+    }
+}
+
+/* The N-1 allgather steps (receive-and-overwrite) over every rail. */
+static void ring_allgather(int e, void *const *buf, uint32_t N, const uint64_t *seg,
+                           uint32_t n_rails, uint64_t *sent_bytes)
+{
+    for (uint32_t s = 0; s + 1 < N; ++s) {
+        for (uint32_t k = 0; k < n_rails; ++k) {
+            const uint64_t *row = seg + (size_t)k * (N + 1);
+            for (uint32_t r = 0; r < N; ++r) {
+                uint32_t j = (r + 1 + N - s) % N;
+                uint32_t d = (r + 1) % N;
+                uint64_t off = row[j], len = row[j + 1] - row[j];
+                memcpy((char *)buf[d] + off * e, (const char *)buf[r] + off * e, len * e);
+                if (sent_bytes) sent_bytes[r] += len * (uint64_t)e;
+            }
+        }
+    }
+}
+
 /*
  * Literal emulation of a ring allreduce run independently on every rail.
  *
@@ -296,40 +332,6 @@ static void add_into(int dtype, void *dst, const void *src, uint64_t off, uint64
  * stop_after_reduce_scatter != 0 returns after the first N-1 steps.
  * sent_bytes[i] (may be NULL) is incremented by what node i puts on the wire.
  */
-static void ring_reduce_scatter(int dtype, int e, void *const *buf, uint32_t N,
-                                const uint64_t *seg, uint32_t n_rails, uint64_t *sent_bytes)
-{
-    for (uint32_t s = 0; s + 1 < N; ++s) {
-        for (uint32_t k = 0; k < n_rails; ++k) {
-            const uint64_t *row = seg + (size_t)k * (N + 1);
-            for (uint32_t r = 0; r < N; ++r) {
-                uint32_t j = (r + N - s) % N;
-                uint32_t d = (r + 1) % N;
-                uint64_t off = row[j], len = row[j + 1] - row[j];
-                add_into(dtype, buf[d], buf[r], off, len);
-                if (sent_bytes) sent_bytes[r] += len * (uint64_t)e;
-            }
-        }
-    }
-}
-
-static void ring_allgather(int e, void *const *buf, uint32_t N, const uint64_t *seg,
-                           uint32_t n_rails, uint64_t *sent_bytes)
-{
-    for (uint32_t s = 0; s + 1 < N; ++s) {
-        for (uint32_t k = 0; k < n_rails; ++k) {
-            const uint64_t *row = seg + (size_t)k * (N + 1);
-            for (uint32_t r = 0; r < N; ++r) {
-                uint32_t j = (r + 1 + N - s) % N;
-                uint32_t d = (r + 1) % N;
-                uint64_t off = row[j], len = row[j + 1] - row[j];
-                memcpy((char *)buf[d] + off * e, (const char *)buf[r] + off * e, len * e);
-                if (sent_bytes) sent_bytes[r] += len * (uint64_t)e;
-            }
-        }
-    }
-}
-
 int orc_ring_allreduce(int dtype, void *const *buf, uint32_t n_nodes, uint64_t n,
                        const uint64_t *seg, uint32_t n_rails,
                        int stop_after_reduce_scatter, uint64_t *sent_bytes)
