@@ -41,7 +41,9 @@ def parse_args():
     p.add_argument("--parts", default="fused,ring,pack,unpack",
                    help="comma list of parts to run in a step (default: all four); also available: "
                         "rs, ag = fused reduce-scatter-only / allgather-only; chunked = Ring_Chunked; "
-                        "failover = fused allreduce with the last rail failing")
+                        "failover = fused allreduce with the last rail failing; "
+                        "packed = fused allreduce, in place, of every rail's contiguous send buffers "
+                        "(the route pack -> allreduce -> unpack; put it between pack and unpack)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--placement", default="spread", choices=["spread", "packed", "torch"],
                    help="where the buffers live in HBM: spread = inputs in the first 96 GiB region, "
@@ -87,6 +89,17 @@ def recorded_traffic(kind: str):
         return None
 
 
+def device_facts(torch):
+    """What the runtime reports about the card (informational; the roofline uses the published peak)."""
+    p = torch.cuda.get_device_properties(0)
+    facts = {"name": p.name, "compute_units": p.multi_processor_count,
+             "hbm_bytes": p.total_memory}
+    for key in ("gcnArchName", "memory_clock_rate", "memory_bus_width", "L2_cache_size"):
+        if hasattr(p, key):
+            facts[key] = getattr(p, key)
+    return facts
+
+
 def cpu_baseline(w, n_sample: int, parts):
     """The oracle, as it stands, on a bounded slice of the same workload (same node count,
     same ratios, n_sample elements per node)."""
@@ -103,7 +116,9 @@ def cpu_baseline(w, n_sample: int, parts):
     seg = orc.segment_map(orc.rail_partition(n, w.ratios, e), N)
     bytes_done = 0
     t0 = time.perf_counter()
-    if "fused" in parts:
+    for p in ("fused", "packed"):        # the packed route sums the same values once more
+        if p not in parts:
+            continue
         if w.dtype == "i32":
             orc.sum_i32(host)
         else:
@@ -205,7 +220,7 @@ def main() -> int:
     tdtype = inputs.TORCH_DTYPE[w.dtype]
     rail_off = nz.nz_rail_partition(n, e, w.ratios)
     seg = nz.nz_segment_map(rail_off, N)
-    need_send = "pack" in parts or "unpack" in parts
+    need_send = any(p in parts for p in ("pack", "unpack", "packed"))
     rail_len = [max(int(rail_off[k + 1] - rail_off[k]), 1) for k in range(R)]
     placement_note = "plain torch allocations"
     arena = placement.try_arena(dev) if args.placement != "torch" else None
@@ -243,7 +258,9 @@ def main() -> int:
                  # optional parts: the two halves on their own, fused form
                  "rs": (N + 1) * S, "ag": N * S,
                  # Ring_Chunked moves the ring's bytes in more launches; failover the fused bytes in two
-                 "chunked": 5 * (N - 1) * S, "failover": 2 * N * S}
+                 "chunked": 5 * (N - 1) * S, "failover": 2 * N * S,
+                 # every rail's N send buffers reduced in place: N reads + N writes of the payload
+                 "packed": 2 * N * S}
 
     def run_part(p):
         if p == "fused":
@@ -258,6 +275,10 @@ def main() -> int:
             nz.nz_allreduce_sim_chunked(ins, n, w.ratios, w.dtype, args.chunk_elems, outs)
         elif p == "failover":
             nz.nz_allreduce_sim_failover(ins, n, w.ratios, w.dtype, "fused", outs, R - 1)
+        elif p == "packed":
+            for k in range(R):
+                if rail_off[k + 1] > rail_off[k]:
+                    nz.nz_allreduce_sim(send[k], int(rail_off[k + 1] - rail_off[k]), (1,), w.dtype, "fused", send[k])
         elif p == "pack":
             for k in range(R):
                 nz.nz_pack(ins, seg, k, ids, e, send[k], send[k][0].numel() * e)
@@ -309,21 +330,27 @@ def main() -> int:
     step_bytes = sum(alg_bytes[p] for p in parts)
     part_stats = {}
     for p in parts:
-        ms = events[p] if args.graph else sum(a.elapsed_time(b) for a, b in events[p]) / len(events[p])
+        if args.graph:
+            ms = med = events[p]
+        else:
+            times = sorted(a.elapsed_time(b) for a, b in events[p])
+            ms = sum(times) / len(times)
+            med = 0.5 * (times[(len(times) - 1) // 2] + times[len(times) // 2])
         gbs = alg_bytes[p] / (ms * 1e-3) / 1e9
-        part_stats[p] = {"ms": round(ms, 4), "payload_GBps": round(S / (ms * 1e-3) / 1e9, 2),
+        part_stats[p] = {"ms": round(ms, 4), "ms_median": round(med, 4), "payload_GBps": round(S / (ms * 1e-3) / 1e9, 2),
                          "hbm_GBps": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4),
                          "algorithmic_bytes": alg_bytes[p]}
 
     head = "fused" if "fused" in parts else parts[0]
     launches = {"fused": 1, "ring": 2 * (N - 1), "pack": R, "unpack": R, "rs": 1, "ag": 1,
-                "chunked": 2 * (N - 1), "failover": 2}[head]
+                "chunked": 2 * (N - 1), "failover": 2, "packed": R}[head]
     achieved = part_stats[head]["hbm_GBps"]
     roofline = {
         "kernel": {"fused": "nz_fused_reduce_bcast", "ring": "nz_ring_step",
                    "pack": "nz_segment_copy", "unpack": "nz_segment_copy",
                    "rs": "nz_fused_reduce_bcast", "ag": "nz_gather_bcast",
-                   "chunked": "nz_ring_step", "failover": "nz_fused_reduce_bcast"}[head],
+                   "chunked": "nz_ring_step", "failover": "nz_fused_reduce_bcast",
+                   "packed": "nz_fused_reduce_bcast"}[head],
         "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
         "algorithmic_bytes_per_launch": alg_bytes[head] // launches,
@@ -347,6 +374,7 @@ def main() -> int:
         "pct_of_hbm_peak": round(100.0 * step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 2),
         "parts": part_stats,
         "roofline": roofline,
+        "device": device_facts(torch),
     }
     if packed_ref_outs is not None:
         # The same fused call with its outputs in the inputs' region, for reference.
