@@ -80,3 +80,21 @@ def test_ratios_feed_the_partition(orc):
     assert b.tolist() == orc.rail_partition(16 * 1024 * 1024, r["ratios"], 4).tolist()
     share = (b[1] - b[0]) / (16 * 1024 * 1024)
     assert share == pytest.approx(r["alpha"][0], abs=1e-4)
+
+
+def test_measured_launch_latencies_as_setup_times(orc):
+    """Two rails whose (T_setup, B) are the fixed cost per call and the asymptotic payload rate
+    measured for the two allreduce modes at 8 nodes (profiles/size_sweep.txt): a real setup
+    time in the sense of Eq. 2, not an invented one."""
+    ts, bw = [8.57e-6, 51.88e-6], [374.42e9, 195.44e9]
+    th = nz.nz_balance_threshold(ts, bw)
+    assert th == pytest.approx((51.88e-6 - 8.57e-6) * 374.42e9, rel=1e-12)     # Eq. 6: about 16.2 MB
+    small = nz.nz_balance(ts, bw, 4e6)                       # below it: everything on the fast-to-start rail
+    assert not small["hot"] and list(small["ratios"]) == [1 << 20, 0]
+    big = nz.nz_balance(ts, bw, 256e6)
+    assert big["hot"]
+    # both rails finish together (Eq. 5 is a maximum: its minimum equalises the two terms)
+    t = [ts[i] + big["alpha"][i] * 256e6 / bw[i] for i in range(2)]
+    assert t[0] == pytest.approx(t[1], rel=1e-9) and big["t_hot"] == pytest.approx(t[0], rel=1e-9)
+    a, t_iter = orc.balance_iterate(ts, bw, 256e6, 30000)
+    assert big["t_hot"] == pytest.approx(t_iter, rel=5e-3) and np.abs(a - big["alpha"]).max() <= 1e-2
