@@ -35,5 +35,24 @@ def build_library(verbose: bool = False) -> str:
     return LIB
 
 
+C_DRIVER_SRC = os.path.join(ROOT, "tests", "c_abi_gpu_driver.cpp")
+C_DRIVER = os.path.join(ROOT, "tests", "libc_abi_gpu_driver.so")
+
+
+def build_c_driver(verbose: bool = False) -> str:
+    """Compile the plain C++ caller of the C ABI that tests/test_gpu_c_abi.py runs on a GPU
+    (host code only; it links the shared library and finds it next to the package)."""
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall",
+           "-Wno-unused-command-line-argument",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-I", os.path.join(ROOT, "include"), C_DRIVER_SRC,
+           "-L", HERE, "-lnezha_sim", "-Wl,-rpath,$ORIGIN/../paper_2405_17870_amd", "-o", C_DRIVER]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.run(cmd, check=True)
+    return C_DRIVER
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_c_driver(verbose=True))
