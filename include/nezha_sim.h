@@ -28,6 +28,11 @@
  *     (NZ_ERR_UNSUPPORTED beyond them).
  *   - Entry points are re-entrant; concurrent calls must not share output
  *     buffers.  Results are bitwise reproducible.
+ *   - Debugging aid: if the environment variable NZ_DEBUG is set to anything
+ *     but "" or "0" at the time of a call, an entry point that takes a
+ *     stream waits for that stream before it returns and reports a
+ *     failure of the execution itself as NZ_ERR_HIP.  Such calls cannot be
+ *     captured in a HIP graph.  It is the library's only global setting.
  */
 #ifndef NEZHA_SIM_H
 #define NEZHA_SIM_H

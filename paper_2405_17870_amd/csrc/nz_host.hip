@@ -9,6 +9,7 @@
 
 #include <algorithm>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <utility>
 #include <vector>
@@ -33,6 +34,22 @@ hipError_t launch(void (*kernel)(const Args), u32 blocks, const Args &args, hipS
 {
     void *params[] = {const_cast<Args *>(&args)};
     return hipLaunchKernel(reinterpret_cast<const void *>(kernel), dim3(blocks), dim3(kThreads), params, 0, st);
+}
+
+// Debugging aid: with NZ_DEBUG set to anything but "" or "0" in the environment
+// (looked up at every call), an entry point waits for its stream before it
+// returns, so a failure during execution is reported by the call that caused it.
+bool debug_sync_enabled()
+{
+    const char *v = std::getenv("NZ_DEBUG");
+    return v != nullptr && v[0] != '\0' && std::strcmp(v, "0") != 0;
+}
+
+nz_status finish(nz_status s, hipStream_t st)
+{
+    if (s != NZ_OK || !debug_sync_enabled()) return s;
+    const hipError_t e = hipStreamSynchronize(st);
+    return e == hipSuccess ? NZ_OK : hip_failed(e, "execution (NZ_DEBUG wait)");
 }
 
 bool aligned256(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
@@ -430,23 +447,28 @@ nz_status nz_allreduce_sim(const void *const *node_bufs, uint32_t n_nodes, uint6
                            const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype, nz_mode mode,
                            void *const *out_bufs, void *stream)
 {
-    return run_collective(kAllreduce, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype, mode, out_bufs,
-                          static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return finish(run_collective(kAllreduce, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype, mode, out_bufs, st),
+                  st);
 }
 
 nz_status nz_reduce_scatter_sim(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
                                 const uint32_t *ratios, uint32_t n_rails, nz_dtype dtype, nz_mode mode,
                                 void *const *out_bufs, void *stream)
 {
-    return run_collective(kReduceScatter, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype, mode,
-                          out_bufs, static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return finish(run_collective(kReduceScatter, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype, mode,
+                                 out_bufs, st),
+                  st);
 }
 
 nz_status nz_allgather_sim(void *const *bufs, uint32_t n_nodes, uint64_t n_elems, const uint32_t *ratios,
                            uint32_t n_rails, nz_dtype dtype, nz_mode mode, void *stream)
 {
-    return run_collective(kAllgather, reinterpret_cast<const void *const *>(bufs), n_nodes, n_elems, ratios,
-                          n_rails, dtype, mode, bufs, static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return finish(run_collective(kAllgather, reinterpret_cast<const void *const *>(bufs), n_nodes, n_elems,
+                                 ratios, n_rails, dtype, mode, bufs, st),
+                  st);
 }
 
 nz_status nz_allreduce_sim_chunked(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
@@ -454,9 +476,11 @@ nz_status nz_allreduce_sim_chunked(const void *const *node_bufs, uint32_t n_node
                                    uint64_t chunk_elems, void *const *out_bufs, void *stream)
 {
     if (chunk_elems == 0) return NZ_ERR_INVALID_ARG;
-    return run_collective(kAllreduce, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype, NZ_RING_STEPWISE,
-                          out_bufs, static_cast<hipStream_t>(stream), 0xffffffffu,
-                          chunk_elems == UINT64_MAX ? UINT64_MAX - 1 : chunk_elems);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return finish(run_collective(kAllreduce, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype,
+                                 NZ_RING_STEPWISE, out_bufs, st, 0xffffffffu,
+                                 chunk_elems == UINT64_MAX ? UINT64_MAX - 1 : chunk_elems),
+                  st);
 }
 
 nz_status nz_allreduce_sim_failover(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,
@@ -484,8 +508,9 @@ nz_status nz_allreduce_sim_failover(const void *const *node_bufs, uint32_t n_nod
     const nz_status first = run_collective(kAllreduce, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype,
                                            mode, out_bufs, st, all & ~(1u << failed_rail));
     if (first != NZ_OK) return first;
-    return run_collective(kAllreduce, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype, mode, out_bufs, st,
-                          1u << failed_rail);
+    return finish(run_collective(kAllreduce, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype, mode, out_bufs,
+                                 st, 1u << failed_rail),
+                  st);
 }
 
 nz_status nz_pack(const void *const *node_bufs, uint32_t n_nodes, const uint64_t *seg_off,
@@ -493,17 +518,20 @@ nz_status nz_pack(const void *const *node_bufs, uint32_t n_nodes, const uint64_t
                   uint32_t elem_bytes, void *const *send_bufs, uint64_t send_capacity_bytes,
                   uint64_t *packed_bytes, void *stream)
 {
-    return segment_copy(node_bufs, send_bufs, n_nodes, seg_off, n_rails, rail, seg_ids, n_segs,
-                        elem_bytes, true, send_capacity_bytes, packed_bytes,
-                        static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return finish(segment_copy(node_bufs, send_bufs, n_nodes, seg_off, n_rails, rail, seg_ids, n_segs,
+                               elem_bytes, true, send_capacity_bytes, packed_bytes, st),
+                  st);
 }
 
 nz_status nz_unpack(const void *const *send_bufs, uint32_t n_nodes, const uint64_t *seg_off,
                     uint32_t n_rails, uint32_t rail, const uint32_t *seg_ids, uint32_t n_segs,
                     uint32_t elem_bytes, void *const *node_bufs, void *stream)
 {
-    return segment_copy(send_bufs, node_bufs, n_nodes, seg_off, n_rails, rail, seg_ids, n_segs,
-                        elem_bytes, false, 0, nullptr, static_cast<hipStream_t>(stream));
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    return finish(segment_copy(send_bufs, node_bufs, n_nodes, seg_off, n_rails, rail, seg_ids, n_segs,
+                               elem_bytes, false, 0, nullptr, st),
+                  st);
 }
 
 }  // extern "C"

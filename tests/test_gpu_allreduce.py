@@ -246,3 +246,23 @@ def test_argument_errors_launch_nothing(orc):
     torch.cuda.synchronize()
     for g, b in zip(outs, before):
         assert torch.equal(g.raw, b)
+
+
+def test_debug_wait_changes_nothing_but_the_timing(orc, monkeypatch):
+    """NZ_DEBUG makes every call wait for its stream; results and statuses stay the same."""
+    N, n, ratios, dtype = 5, 40_001, (3, 1), "bf16"
+    host = _host_inputs(dtype, N, n, seed=77)
+    ins = gu.device_inputs(host, dtype)
+    ref, dbg = gu.fresh_outputs(N, n, dtype), gu.fresh_outputs(N, n, dtype)
+    for mode in ("fused", "ring-stepwise"):
+        nz.nz_allreduce_sim([g.t for g in ins], n, ratios, dtype, mode, [g.t for g in ref])
+        torch.cuda.synchronize()
+        monkeypatch.setenv("NZ_DEBUG", "1")
+        nz.nz_allreduce_sim([g.t for g in ins], n, ratios, dtype, mode, [g.t for g in dbg])
+        got = [g.host() for g in dbg]
+        with pytest.raises(nz.NezhaSimError) as ex:
+            nz.nz_allreduce_sim([g.t for g in ins], n, (0, 0), dtype, mode, [g.t for g in dbg])
+        assert ex.value.status == 1
+        monkeypatch.setenv("NZ_DEBUG", "0")
+        for a, b in zip(got, ref):
+            assert np.array_equal(a, b.host())
