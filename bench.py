@@ -194,7 +194,7 @@ def size_sweep(torch, nz, dev) -> int:
 def main() -> int:
     args = parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (the N simulated nodes share one "
+        print("bench.py: the library runs on exactly one GPU (the N simulated nodes share one "
               "MI355X's HBM); --gpus must be 1", file=sys.stderr)
         return 2
 
