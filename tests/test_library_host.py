@@ -95,3 +95,13 @@ def test_bench_refuses_more_than_one_gpu():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
                        capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_missing_library_raises_and_nothing_falls_back(monkeypatch, tmp_path):
+    """Without the built shared library every call raises: there is no other implementation."""
+    monkeypatch.setattr(nz, "_lib", None)
+    monkeypatch.setattr(nz, "LIB_PATH", str(tmp_path / "libnezha_sim.so"))
+    with pytest.raises(RuntimeError, match="is missing"):
+        nz.nz_rail_partition(1000, 4, (1, 1))
+    with pytest.raises(RuntimeError, match="is missing"):
+        nz.nz_allreduce_sim([0], 1, (1,), "f32", "fused", [0])
