@@ -574,6 +574,39 @@ double orc_balance_iterate(uint32_t n_rails, const double *t_setup, const double
     return best_t;
 }
 
+/* ---------------------------------------------------------------------- */
+/* Network efficiency and the efficiency ratio (Sec. 2.1.2 Eq. 2,          */
+/* Sec. 2.2.1 Eq. 3)                                                       */
+/* ---------------------------------------------------------------------- */
+
+/*
+ * Eq. 2: efficiency of one network on a message of S bytes,
+ *   delta = T_theoretical / T_actual = 1 / (1 + T_setup / (S / B)),
+ * with T_theoretical = S / B the transmission time without overheads.
+ * S must be positive.
+ */
+double orc_net_efficiency(double t_setup, double bw, double S)
+{
+    double t_theoretical = S / bw;
+    return 1.0 / (1.0 + t_setup / t_theoretical);
+}
+
+/*
+ * Eq. 3: real-time efficiency ratio of networks i and j that carry S_i and
+ * S_j bytes of one message,
+ *   rho = (S_i * delta_i / That_i) / (S_j * delta_j / That_j),
+ * delta from Eq. 2 at the network's own volume and That = S / B its ideal
+ * transmission time: numerator and denominator are the two networks'
+ * throughputs at that moment.  S_i, S_j must be positive.
+ */
+double orc_efficiency_ratio(double t_setup_i, double bw_i, double S_i,
+                            double t_setup_j, double bw_j, double S_j)
+{
+    double num = S_i * orc_net_efficiency(t_setup_i, bw_i, S_i) / (S_i / bw_i);
+    double den = S_j * orc_net_efficiency(t_setup_j, bw_j, S_j) / (S_j / bw_j);
+    return num / den;
+}
+
 #ifdef _OPENMP
 #include <omp.h>
 int orc_threads(void) { return omp_get_max_threads(); }

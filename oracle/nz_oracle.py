@@ -28,7 +28,7 @@ __all__ = [
     "F32", "BF16", "F16", "I32", "ELEM_BYTES", "build", "threads",
     "rail_partition", "segment_map", "sum_float", "sum_i32", "round_to_storage",
     "ring_allreduce", "ring_allgather", "ring_allreduce_chunked", "failover_target", "pack", "unpack",
-    "t_cold", "t_hot", "balance_iterate",
+    "t_cold", "t_hot", "balance_iterate", "net_efficiency", "efficiency_ratio",
     "bf16_to_f32", "f32_to_bf16", "f16_to_f32", "f32_to_f16", "storage_dtype",
 ]
 
@@ -67,6 +67,10 @@ def _L():
         lib.orc_t_hot.restype = dbl
         lib.orc_balance_iterate.argtypes = [u32, vp, vp, dbl, u32, vp]
         lib.orc_balance_iterate.restype = dbl
+        lib.orc_net_efficiency.argtypes = [dbl, dbl, dbl]
+        lib.orc_net_efficiency.restype = dbl
+        lib.orc_efficiency_ratio.argtypes = [dbl] * 6
+        lib.orc_efficiency_ratio.restype = dbl
         lib.orc_pack.argtypes = [vp, vp, u32, u32, vp, u32, u32, vp, vp]
         lib.orc_unpack.argtypes = [vp, vp, u32, u32, vp, u32, u32, vp]
         lib.orc_bf16_to_f32.argtypes = [ctypes.c_uint16]
@@ -261,6 +265,21 @@ def balance_iterate(t_setup, bw, S: float, iterations: int = 20000) -> Tuple[np.
     if t < 0:
         raise ValueError("oracle: balance_iterate: invalid argument")
     return a, float(t)
+
+
+def net_efficiency(t_setup: float, bw: float, S: float) -> float:
+    """Eq. 2: T_theoretical / T_actual of one network on S bytes (S > 0)."""
+    assert S > 0 and bw > 0
+    f = _L().orc_net_efficiency
+    return float(f(float(t_setup), float(bw), float(S)))
+
+
+def efficiency_ratio(t_setup_i: float, bw_i: float, S_i: float,
+                     t_setup_j: float, bw_j: float, S_j: float) -> float:
+    """Eq. 3: throughput of network i on S_i bytes over that of network j on S_j bytes."""
+    assert S_i > 0 and S_j > 0
+    f = _L().orc_efficiency_ratio
+    return float(f(float(t_setup_i), float(bw_i), float(S_i), float(t_setup_j), float(bw_j), float(S_j)))
 
 
 def pack(node_buf: np.ndarray, seg: np.ndarray, rail: int, seg_ids: Sequence[int],

@@ -119,3 +119,55 @@ def test_eq5_reproduces_the_printed_split_latencies_of_table1(orc):
     assert orc.t_cold(ts, bw, small)[0] * 1e6 < 0.02 * min(tab[small][2:])
     # swapping the shares of the 99:1 column gives the 1:99 column, not the 99:1 one
     assert orc.t_hot(ts, bw, large, (0.01, 0.99)) * 1e6 != pytest.approx(tab[large][3], rel=0.12)
+
+
+def test_eq2_network_efficiency_closed_forms(orc):
+    # T_setup equal to the transmission time halves the efficiency; three times it quarters it
+    assert orc.net_efficiency(1e-3, 1e9, 1e6) == pytest.approx(0.5, rel=1e-15)
+    assert orc.net_efficiency(3e-3, 1e9, 1e6) == pytest.approx(0.25, rel=1e-15)
+    assert orc.net_efficiency(0.0, 1e9, 1e6) == 1.0
+    # it is T_theoretical / T_actual, and grows with the message size towards one
+    for ts, bw, S in [(9e-6, 0.37e9, 1024.0), (982e-6, 0.21e9, 8.0 * 2 ** 20), (5e-5, 12e9, 3e7)]:
+        assert orc.net_efficiency(ts, bw, S) == pytest.approx((S / bw) / (ts + S / bw), rel=1e-14)
+        assert orc.net_efficiency(ts, bw, S) < orc.net_efficiency(ts, bw, 2 * S) < 1.0
+    # half efficiency exactly at S = T_setup * B
+    assert orc.net_efficiency(982e-6, 0.2e9, 982e-6 * 0.2e9) == pytest.approx(0.5, rel=1e-14)
+
+
+def test_eq3_efficiency_ratio_is_a_ratio_of_throughputs(orc):
+    from fractions import Fraction as Fr
+    cases = [((Fr(1, 1000), Fr(10 ** 9), Fr(4 * 10 ** 6)), (Fr(4, 1000), Fr(4 * 10 ** 9), Fr(12 * 10 ** 6))),
+             ((Fr(9, 10 ** 6), Fr(37 * 10 ** 7), Fr(512)), (Fr(982, 10 ** 6), Fr(21 * 10 ** 7), Fr(512)))]
+    for (ti, bi, si), (tj, bj, sj) in cases:
+        exact = (si / (ti + si / bi)) / (sj / (tj + sj / bj))          # bytes per second over bytes per second
+        got = orc.efficiency_ratio(float(ti), float(bi), float(si), float(tj), float(bj), float(sj))
+        assert got == pytest.approx(float(exact), rel=1e-13)
+        back = orc.efficiency_ratio(float(tj), float(bj), float(sj), float(ti), float(bi), float(si))
+        assert got * back == pytest.approx(1.0, rel=1e-13)
+    # hand case: 4 MB on (1 ms, 1 GB/s) takes 5 ms -> 0.8 GB/s; 12 MB on (4 ms, 4 GB/s) takes 7 ms -> 12/7 GB/s
+    assert orc.efficiency_ratio(1e-3, 1e9, 4e6, 4e-3, 4e9, 12e6) == pytest.approx(0.8 / (12 / 7), rel=1e-13)
+    # identical networks with equal volumes: the homogeneous case, rho = 1
+    assert orc.efficiency_ratio(2e-4, 1e9, 5e6, 2e-4, 1e9, 5e6) == 1.0
+
+
+def test_eq3_against_table1_and_the_tolerance_threshold(orc):
+    """Table 1 again: the two single-rail columns are each network's latency on the whole
+    message, so their quotient is the measured efficiency ratio.  It is far above the paper's
+    tolerance threshold (tau = 5, Sec. 2.2.1) at 1 KB, where the table shows that no split
+    helps, and below it at 8 MB and 64 MB, where the 1:1 split beats both single rails."""
+    tab = _table1()
+    small, large = min(tab), max(tab)
+    tau = 5.0
+
+    def fit(col):
+        t1, t2 = tab[small][col] * 1e-6, tab[large][col] * 1e-6
+        b = (large - small) / (t2 - t1)
+        return t1 - small / b, b
+
+    (ts_s, b_s), (ts_t, b_t) = fit(0), fit(1)
+    for S, row in tab.items():
+        measured = row[1] / row[0]                                   # SHARP's throughput over TCP's
+        rho = orc.efficiency_ratio(ts_s, b_s, S, ts_t, b_t, S)
+        assert rho == pytest.approx(measured, rel=0.08), S
+        split_helps = row[2] < min(row[0], row[1])
+        assert (rho <= tau) == split_helps, S
