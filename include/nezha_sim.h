@@ -252,6 +252,32 @@ nz_status nz_balance_threshold(const nz_rail_model *rails, uint32_t n_rails,
                                double *threshold_bytes);
 
 /*
+ * Network efficiency and the real-time efficiency ratio.  (Sec. 2.1.2, Eq. 2:
+ * delta = T_theoretical / T_actual = 1 / (1 + T_setup / (S / B)).  Sec. 2.2.1,
+ * Eq. 3: rho = (S_i delta_i / That_i) / (S_j delta_j / That_j), the quotient
+ * of the throughputs of two networks that carry S_i and S_j bytes of one
+ * message; data is split across rails only while rho does not exceed the
+ * tolerance threshold tau, which the paper sets to 5.)
+ *
+ * Host only.
+ * nz_net_efficiency: *delta receives Eq. 2 for one rail on msg_bytes > 0.
+ * nz_efficiency_ratio: rail i carries alpha[i] * msg_bytes (alpha: host,
+ * n_rails shares >= 0 with a positive sum, normalised to sum one; NULL = an
+ * even split).  *rho receives the largest quotient of Eq. 3 over the pairs of
+ * rails that carry something, i.e. the highest throughput over the lowest
+ * (>= 1; exactly 1 when fewer than two rails carry data).  Whether to split is
+ * the caller's decision: compare *rho with NZ_TOLERANCE_TAU.
+ * NZ_ERR_INVALID_ARG: a null pointer, an invalid model, msg_bytes not positive
+ * and finite, a negative or non-finite share, all shares zero.
+ */
+#define NZ_TOLERANCE_TAU 5.0
+
+nz_status nz_net_efficiency(const nz_rail_model *rail, double msg_bytes, double *delta);
+
+nz_status nz_efficiency_ratio(const nz_rail_model *rails, uint32_t n_rails, double msg_bytes,
+                              const double *alpha, double *rho);
+
+/*
  * Pack: stage rail segments into contiguous send buffers.  (Sec. 3.2: data
  * moves from the user's UnboundBuffer into a rail's contiguous Buffer.)
  *

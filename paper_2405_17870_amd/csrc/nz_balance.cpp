@@ -12,6 +12,9 @@
 // rail that takes part finishes at the same time T and every rail whose
 // startup latency alone exceeds T sits out ("water filling" over the startup
 // latencies).  That closed form is what is computed here; no iteration.
+//
+// Sec. 2.1.2 Eq. 2 (network efficiency) and Sec. 2.2.1 Eq. 3 (the real-time
+// efficiency ratio that gates splitting) are evaluated at the end of the file.
 #include <algorithm>
 #include <cmath>
 #include <limits>
@@ -147,6 +150,44 @@ nz_status nz_balance_threshold(const nz_rail_model *rails, uint32_t n_rails, dou
     const std::vector<uint32_t> order = by_setup(rails, n_rails);
     const nz_rail_model &first = rails[order[0]], &second = rails[order[1]];
     *threshold_bytes = (second.setup_s - first.setup_s) * first.bytes_per_s;
+    return NZ_OK;
+}
+
+nz_status nz_net_efficiency(const nz_rail_model *rail, double msg_bytes, double *delta)
+{
+    if (!valid_model(rail, 1) || delta == nullptr) return NZ_ERR_INVALID_ARG;
+    if (!(msg_bytes > 0.0) || !std::isfinite(msg_bytes)) return NZ_ERR_INVALID_ARG;
+    // Eq. 2, with numerator and denominator multiplied by S / B.
+    const double wire = msg_bytes / rail->bytes_per_s;
+    *delta = wire / (wire + rail->setup_s);
+    return NZ_OK;
+}
+
+nz_status nz_efficiency_ratio(const nz_rail_model *rails, uint32_t n_rails, double msg_bytes,
+                              const double *alpha, double *rho)
+{
+    if (n_rails > NZ_MAX_RAILS) return NZ_ERR_UNSUPPORTED;
+    if (!valid_model(rails, n_rails) || rho == nullptr) return NZ_ERR_INVALID_ARG;
+    if (!(msg_bytes > 0.0) || !std::isfinite(msg_bytes)) return NZ_ERR_INVALID_ARG;
+    double total = 0.0;
+    for (uint32_t i = 0; i < n_rails && alpha != nullptr; ++i) {
+        if (!(alpha[i] >= 0.0) || !std::isfinite(alpha[i])) return NZ_ERR_INVALID_ARG;
+        total += alpha[i];
+    }
+    if (alpha != nullptr && !(total > 0.0)) return NZ_ERR_INVALID_ARG;
+    // S_i * delta_i / That_i of Eq. 3 is the rail's throughput on its own
+    // volume: S_i / (T_setup_i + S_i / B_i).
+    double fastest = 0.0, slowest = 0.0;
+    bool any = false;
+    for (uint32_t i = 0; i < n_rails; ++i) {
+        const double volume = msg_bytes * (alpha ? alpha[i] / total : 1.0 / n_rails);
+        if (!(volume > 0.0)) continue;
+        const double rate = volume / (rails[i].setup_s + volume / rails[i].bytes_per_s);
+        fastest = any ? std::max(fastest, rate) : rate;
+        slowest = any ? std::min(slowest, rate) : rate;
+        any = true;
+    }
+    *rho = fastest / slowest;
     return NZ_OK;
 }
 

@@ -34,6 +34,7 @@ EXPORTS = [
     "nz_rail_partition_ex", "nz_segment_map", "nz_allreduce_sim", "nz_reduce_scatter_sim",
     "nz_allgather_sim", "nz_allreduce_sim_chunked", "nz_failover_target",
     "nz_allreduce_sim_failover", "nz_pack", "nz_unpack", "nz_balance", "nz_balance_threshold",
+    "nz_net_efficiency", "nz_efficiency_ratio",
 ]
 
 
@@ -86,6 +87,10 @@ def load() -> ctypes.CDLL:
     lib.nz_balance.restype = i32
     lib.nz_balance_threshold.argtypes = [vp, u32, vp]
     lib.nz_balance_threshold.restype = i32
+    lib.nz_net_efficiency.argtypes = [vp, ctypes.c_double, vp]
+    lib.nz_net_efficiency.restype = i32
+    lib.nz_efficiency_ratio.argtypes = [vp, u32, ctypes.c_double, vp, vp]
+    lib.nz_efficiency_ratio.restype = i32
     _lib = lib
     return lib
 
@@ -282,4 +287,31 @@ def nz_balance_threshold(setup_s: Sequence[float], bytes_per_s: Sequence[float])
     lib = load()
     out = ctypes.c_double(0)
     _check(lib.nz_balance_threshold(_models(setup_s, bytes_per_s), len(setup_s), ctypes.byref(out)))
+    return out.value
+
+
+NZ_TOLERANCE_TAU = 5.0
+
+
+def nz_net_efficiency(setup_s: float, bytes_per_s: float, msg_bytes: float) -> float:
+    """Network efficiency of one rail on a message (Sec. 2.1.2, Eq. 2).  Host only."""
+    lib = load()
+    out = ctypes.c_double(0)
+    _check(lib.nz_net_efficiency(_models([setup_s], [bytes_per_s]), float(msg_bytes), ctypes.byref(out)))
+    return out.value
+
+
+def nz_efficiency_ratio(setup_s: Sequence[float], bytes_per_s: Sequence[float], msg_bytes: float,
+                        alpha: Optional[Sequence[float]] = None) -> float:
+    """Real-time efficiency ratio of the rails under the given shares (Sec. 2.2.1, Eq. 3):
+    highest throughput over lowest; splitting pays only while it stays below tau = 5."""
+    lib = load()
+    a = None
+    if alpha is not None:
+        if len(alpha) != len(setup_s):
+            raise ValueError("one share per rail")
+        a = (ctypes.c_double * max(len(alpha), 1))(*[float(x) for x in alpha])
+    out = ctypes.c_double(0)
+    _check(lib.nz_efficiency_ratio(_models(setup_s, bytes_per_s), len(setup_s), float(msg_bytes), a,
+                                   ctypes.byref(out)))
     return out.value

@@ -97,6 +97,13 @@ int main()
         REQUIRE(th <= tc * (1 + 1e-12) && best < R);
         REQUIRE(nz_balance_threshold(m.data(), R, &thr) == NZ_OK && thr >= 0.0);
         REQUIRE((hot != 0) == (S > thr));
+        // Eq. 2 and Eq. 3 on the same model, with the balancer's own shares and with an even split
+        double delta = -1.0, rho = -1.0;
+        if (S > 0.0) {
+            REQUIRE(nz_net_efficiency(&m[0], S, &delta) == NZ_OK && delta > 0.0 && delta <= 1.0);
+            REQUIRE(nz_efficiency_ratio(m.data(), R, S, alpha.data(), &rho) == NZ_OK && rho >= 1.0);
+            REQUIRE(nz_efficiency_ratio(m.data(), R, S, nullptr, &rho) == NZ_OK && rho >= 1.0);
+        }
     }
 
     // hostile arguments: nothing may be written or read out of bounds, only statuses returned
@@ -121,6 +128,14 @@ int main()
     REQUIRE(nz_balance(&one, 1, 1.0, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr) == NZ_OK);
     REQUIRE(nz_balance(nullptr, 1, 1.0, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr) == NZ_ERR_INVALID_ARG);
     REQUIRE(nz_balance(&one, 9, 1.0, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr) == NZ_ERR_UNSUPPORTED);
+    double d = 0.0;
+    const double zero_shares[1] = {0.0};
+    REQUIRE(nz_net_efficiency(nullptr, 1.0, &d) == NZ_ERR_INVALID_ARG);
+    REQUIRE(nz_net_efficiency(&one, 1.0, nullptr) == NZ_ERR_INVALID_ARG);
+    REQUIRE(nz_net_efficiency(&one, 0.0, &d) == NZ_ERR_INVALID_ARG);
+    REQUIRE(nz_efficiency_ratio(&one, 1, 1.0, zero_shares, &d) == NZ_ERR_INVALID_ARG);
+    REQUIRE(nz_efficiency_ratio(&one, 9, 1.0, nullptr, &d) == NZ_ERR_UNSUPPORTED);
+    REQUIRE(nz_efficiency_ratio(&one, 1, 1.0, nullptr, &d) == NZ_OK && d == 1.0);
     for (int st = 0; st < 8; ++st) REQUIRE(nz_status_str((nz_status)st) != nullptr);
     std::puts("host sanitizer run ok");
     return 0;

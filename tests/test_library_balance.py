@@ -98,3 +98,29 @@ def test_measured_launch_latencies_as_setup_times(orc):
     assert t[0] == pytest.approx(t[1], rel=1e-9) and big["t_hot"] == pytest.approx(t[0], rel=1e-9)
     a, t_iter = orc.balance_iterate(ts, bw, 256e6, 30000)
     assert big["t_hot"] == pytest.approx(t_iter, rel=5e-3) and np.abs(a - big["alpha"]).max() <= 1e-2
+
+
+def test_efficiency_and_ratio_match_the_oracle(orc):
+    rnd = random.Random(3)
+    for _ in range(200):
+        R = rnd.randint(1, 8)
+        ts, bw = _random_model(rnd, R)
+        S = 10 ** rnd.uniform(2, 9)
+        assert nz.nz_net_efficiency(ts[0], bw[0], S) == pytest.approx(orc.net_efficiency(ts[0], bw[0], S), rel=1e-13)
+        alpha = [rnd.choice([0.0, rnd.random()]) for _ in range(R)]
+        if sum(alpha) == 0.0:
+            alpha[rnd.randrange(R)] = 1.0
+        for shares in (None, alpha):
+            a = [1.0 / R] * R if shares is None else [x / sum(alpha) for x in alpha]
+            live = [i for i in range(R) if a[i] > 0]
+            want = max([orc.efficiency_ratio(ts[i], bw[i], a[i] * S, ts[j], bw[j], a[j] * S)
+                        for i in live for j in live if i != j], default=1.0)
+            assert nz.nz_efficiency_ratio(ts, bw, S, shares) == pytest.approx(want, rel=1e-12)
+    assert nz.nz_efficiency_ratio([2e-4] * 3, [1e9] * 3, 6e6) == 1.0        # homogeneous rails
+    assert nz.NZ_TOLERANCE_TAU == 5.0
+    for bad in (lambda: nz.nz_net_efficiency(1e-3, 1e9, 0.0), lambda: nz.nz_net_efficiency(1e-3, 0.0, 1e6),
+                lambda: nz.nz_efficiency_ratio([1e-3, 1e-3], [1e9, 1e9], 1e6, [0.0, 0.0]),
+                lambda: nz.nz_efficiency_ratio([1e-3, 1e-3], [1e9, 1e9], 1e6, [-1.0, 2.0]),
+                lambda: nz.nz_efficiency_ratio([1e-3], [1e9], float("inf"))):
+        with pytest.raises(nz.NezhaSimError):
+            bad()
