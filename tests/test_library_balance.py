@@ -86,9 +86,9 @@ def test_measured_launch_latencies_as_setup_times(orc):
     """Two rails whose (T_setup, B) are the fixed cost per call and the asymptotic payload rate
     measured for the two allreduce modes at 8 nodes (profiles/size_sweep.txt): a real setup
     time in the sense of Eq. 2, not an invented one."""
-    ts, bw = [8.57e-6, 51.88e-6], [374.42e9, 195.44e9]
+    ts, bw = [8.37e-6, 49.28e-6], [373.57e9, 193.24e9]
     th = nz.nz_balance_threshold(ts, bw)
-    assert th == pytest.approx((51.88e-6 - 8.57e-6) * 374.42e9, rel=1e-12)     # Eq. 6: about 16.2 MB
+    assert th == pytest.approx((49.28e-6 - 8.37e-6) * 373.57e9, rel=1e-12)     # Eq. 6: about 15.3 MB
     small = nz.nz_balance(ts, bw, 4e6)                       # below it: everything on the fast-to-start rail
     assert not small["hot"] and list(small["ratios"]) == [1 << 20, 0]
     big = nz.nz_balance(ts, bw, 256e6)
