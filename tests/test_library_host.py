@@ -105,3 +105,26 @@ def test_missing_library_raises_and_nothing_falls_back(monkeypatch, tmp_path):
         nz.nz_rail_partition(1000, 4, (1, 1))
     with pytest.raises(RuntimeError, match="is missing"):
         nz.nz_allreduce_sim([0], 1, (1,), "f32", "fused", [0])
+
+
+def test_work_that_does_not_fit_a_grid_is_refused_before_any_launch():
+    """Validation is pure host arithmetic and precedes every HIP call: with made-up (aligned,
+    far apart) addresses a message of 2^43 elements is refused as unsupported, an empty one
+    accepted, without a device.  (Skipped where a GPU is visible: the addresses are not real.)"""
+    import torch
+    if torch.cuda.device_count() > 0:
+        pytest.skip("made-up device addresses: host-only check")
+    ins, outs = [1 << 46, 1 << 47], [1 << 48, 1 << 49]
+    for mode in ("fused", "ring-stepwise"):
+        with pytest.raises(nz.NezhaSimError) as ex:
+            nz.nz_allreduce_sim(ins, 1 << 43, (1, 1), "f32", mode, outs, stream=_NullStream())
+        assert ex.value.status == 3
+        nz.nz_allreduce_sim(ins, 0, (1, 1), "f32", mode, outs, stream=_NullStream())
+    with pytest.raises(nz.NezhaSimError) as ex:              # overlapping made-up buffers
+        nz.nz_allreduce_sim(ins, 1 << 43, (1, 1), "f32", "fused", [(1 << 46) + 256, 1 << 49],
+                            stream=_NullStream())
+    assert ex.value.status == 3
+
+
+class _NullStream:
+    cuda_stream = 0
