@@ -193,6 +193,9 @@ def size_sweep(torch, nz, dev) -> int:
 
 def main() -> int:
     args = parse_args()
+    if args.steps < 1 or args.warmup < 0:
+        print("bench.py: --steps must be at least 1 and --warmup at least 0", file=sys.stderr)
+        return 2
     if args.gpus != 1:
         print("bench.py: the library runs on exactly one GPU (the N simulated nodes share one "
               "MI355X's HBM); --gpus must be 1", file=sys.stderr)
