@@ -62,7 +62,8 @@ def parse_args():
                    help="segment list of pack/unpack: the whole rail in order (one aligned run per "
                         "node) or the order a node sends its segments in (misaligned runs: the re-alignment path)")
     p.add_argument("--graph", action="store_true",
-                   help="capture one step in a HIP graph and time its replays (no per-part times)")
+                   help="capture one step in a HIP graph and time its replays (no per-part times); "
+                        "with --sweep: capture the calls of each size and time the replay")
     p.add_argument("--sweep", action="store_true",
                    help="instead of the step: time fused and ring-stepwise allreduce over message sizes "
                         "2 KB .. 64 MB (fp32, 2 rails 1:1) at 4 and 8 nodes and print one JSON line")
@@ -148,11 +149,13 @@ def cpu_baseline(w, n_sample: int, parts):
     }
 
 
-def size_sweep(torch, nz, dev) -> int:
+def size_sweep(torch, nz, dev, use_graph: bool = False) -> int:
     """Latency and payload throughput (message bytes / time, the paper's definition) of one
     allreduce per message size, the range of the paper's allreduce benchmark.  The fit
     t = t0 + S / B per mode gives the fixed cost per call and the asymptotic payload rate,
-    the two quantities of the paper's network efficiency model (Sec. 2.1.2, Eq. 2)."""
+    the two quantities of the paper's network efficiency model (Sec. 2.1.2, Eq. 2).
+    With use_graph the calls of one size are captured in a HIP graph and its replay is timed:
+    the fixed cost is then the GPU's per launch, without the host's per call."""
     rows = []
     for N in (4, 8):
         for log2 in range(11, 27):
@@ -167,10 +170,21 @@ def size_sweep(torch, nz, dev) -> int:
                     nz.nz_allreduce_sim(ins, n, (1, 1), "f32", mode, outs)
                 torch.cuda.synchronize()
                 a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record()
-                for _ in range(reps):
-                    nz.nz_allreduce_sim(ins, n, (1, 1), "f32", mode, outs)
-                b.record()
+                if use_graph:
+                    graph = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(graph):
+                        for _ in range(reps):
+                            nz.nz_allreduce_sim(ins, n, (1, 1), "f32", mode, outs)
+                    graph.replay()
+                    torch.cuda.synchronize()
+                    a.record()
+                    graph.replay()
+                    b.record()
+                else:
+                    a.record()
+                    for _ in range(reps):
+                        nz.nz_allreduce_sim(ins, n, (1, 1), "f32", mode, outs)
+                    b.record()
                 torch.cuda.synchronize()
                 us = a.elapsed_time(b) * 1e3 / reps
                 row[mode] = {"us": round(us, 2), "payload_GBps": round(S / us / 1e3, 3)}
@@ -187,7 +201,8 @@ def size_sweep(torch, nz, dev) -> int:
             t0 = (sy - slope * sx) / m
             fits[f"{mode}_N{N}"] = {"t0_us": round(t0, 2), "payload_GBps": round(1.0 / slope / 1e3, 2),
                                     "half_efficiency_bytes": int(t0 / slope)}
-    print(json.dumps({"sweep": rows, "fit_t_equals_t0_plus_S_over_B": fits}), flush=True)
+    print(json.dumps({"sweep": rows, "hip_graph": use_graph, "fit_t_equals_t0_plus_S_over_B": fits}),
+          flush=True)
     return 0
 
 
@@ -213,7 +228,7 @@ def main() -> int:
     dev = "cuda:0"
     torch.cuda.set_device(0)
     if args.sweep:
-        return size_sweep(torch, nz, dev)
+        return size_sweep(torch, nz, dev, args.graph)
     w = inputs.WORKLOADS[args.workload]
     parts = [p for p in args.parts.split(",") if p]
     N, n, e = w.n_nodes, w.n_elems, inputs.ELEM_BYTES[w.dtype]
