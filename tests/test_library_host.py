@@ -128,3 +128,33 @@ def test_work_that_does_not_fit_a_grid_is_refused_before_any_launch():
 
 class _NullStream:
     cuda_stream = 0
+
+
+def test_binding_marshals_what_the_header_declares():
+    """Every prototype of the header against the binding's ctypes signature: same number of
+    parameters, and the same kind (pointer, 32-bit, 64-bit, double) in every position."""
+    header = open(os.path.join(ROOT, "include", "nezha_sim.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    protos = re.findall(r"\b(nz_[a-z0-9_]+)\s*\(([^)]*)\)\s*;", header)
+    assert len(protos) == len(nz.EXPORTS)
+    lib = nz.load()
+
+    def kind(param: str) -> str:
+        p = param.strip()
+        if p == "void" or not p:
+            return ""
+        if "*" in p:
+            return "ptr"
+        if p.startswith("uint64_t"):
+            return "u64"
+        if p.startswith("double"):
+            return "f64"
+        assert p.split()[0] in ("uint32_t", "nz_status", "nz_dtype", "nz_mode", "int"), p
+        return "w32"
+
+    ctype_kind = {ctypes.c_void_p: "ptr", ctypes.c_uint64: "u64", ctypes.c_double: "f64",
+                  ctypes.c_uint32: "w32", ctypes.c_int: "w32"}
+    for name, params in protos:
+        want = [k for k in (kind(p) for p in params.split(",")) if k]
+        got = [ctype_kind[t] for t in getattr(lib, name).argtypes]
+        assert got == want, name
