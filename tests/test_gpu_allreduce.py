@@ -266,3 +266,20 @@ def test_debug_wait_changes_nothing_but_the_timing(orc, monkeypatch):
         monkeypatch.setenv("NZ_DEBUG", "0")
         for a, b in zip(got, ref):
             assert np.array_equal(a, b.host())
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_cold_start_ratios_equal_the_single_rail_ring(orc, dtype):
+    """All data on one rail (Sec. 4.3, Eq. 4) is written as weights {1, 0, ..}: in ring mode too
+    the result is bitwise the single-rail result, wherever the loaded rail sits in the list."""
+    N, n = 7, 90_001
+    host = _host_inputs(dtype, N, n, seed=13, std=1.0)
+    ins = gu.device_inputs(host, dtype)
+    single = gu.fresh_outputs(N, n, dtype)
+    gu.allreduce(ins, single, (1,), "ring-stepwise")
+    for ratios in [(1, 0), (0, 1), (0, 5, 0, 0)]:
+        out = gu.fresh_outputs(N, n, dtype)
+        gu.allreduce(ins, out, ratios, "ring-stepwise")
+        for a, b in zip(out, single):
+            assert np.array_equal(a.host(), b.host()), ratios
+            assert a.guards_intact()
