@@ -179,10 +179,13 @@ nz_status nz_allgather_sim(void *const *bufs, uint32_t n_nodes, uint64_t n_elems
  *
  * The ring of NZ_RING_STEPWISE with every segment transfer cut into pieces of
  * at most chunk_elems elements (> 0): each of the 2 (N - 1) steps is issued as
- * one launch per piece, piece c of every (rail, node) before piece c + 1.
- * Every element goes through the same additions in the same order as in
- * NZ_RING_STEPWISE, so the result is bitwise that mode's; what changes is
- * the number of launches, ceil(longest segment / chunk_elems) per step.
+ * one launch per piece.  Pieces cover disjoint elements, so a piece's step
+ * depends on that piece's previous step only; the launches go piece by piece
+ * (all steps of piece c of every (rail, node), then piece c + 1), the order in
+ * which a pipeline moves each piece.  Every element goes through the same
+ * additions in the same order as in NZ_RING_STEPWISE, so the result is bitwise
+ * that mode's; what changes is the number of launches,
+ * ceil(longest segment / chunk_elems) per step.
  * Arguments, aliasing rules and errors as nz_allreduce_sim in ring mode.
  */
 nz_status nz_allreduce_sim_chunked(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,

@@ -167,25 +167,26 @@ enum Collective { kAllreduce, kReduceScatter, kAllgather };
 constexpr u64 kRingReuseBytes = 128ull << 20;
 
 // The launches of a ring: N - 1 reduce-scatter steps, then N - 1 allgather
-// steps (one half only for the phase collectives).  n_pieces > 1: every step
-// is issued as n_pieces launches, piece c of every segment before piece c + 1
-// (a.g.win_len elements each).
+// steps (one half only for the phase collectives).  n_pieces > 1 (Ring_Chunked):
+// every step is issued as n_pieces launches of a.g.win_len elements of every
+// segment each.  Pieces cover disjoint elements, so a piece's next step
+// depends on that piece's previous step only; the launches go piece by piece
+// (all steps of piece 0, then all steps of piece 1, ...), which is the order a
+// pipeline gives each piece and lets a piece's partial sums stay in cache
+// from the step that stores them to the step that sends them on.
 template <class T, bool REUSE>
 nz_status launch_ring_steps(RingArgs &a, u32 blocks, hipStream_t st, Collective what, u64 n_pieces)
 {
     const u32 N = a.g.n_nodes;
-    for (u32 s = 0; s + 1 < N && what != kAllgather; ++s) {
-        a.step = s;
-        for (u64 c = 0; c < n_pieces; ++c) {
-            a.g.win_off = c * (n_pieces > 1 ? a.g.win_len : 0);
+    for (u64 c = 0; c < n_pieces; ++c) {
+        a.g.win_off = c * (n_pieces > 1 ? a.g.win_len : 0);
+        for (u32 s = 0; s + 1 < N && what != kAllgather; ++s) {
+            a.step = s;
             const hipError_t e = launch(nz_ring_step<T, kRingIters, false, REUSE>, blocks, a, st);
             if (e != hipSuccess) return hip_failed(e, "ring reduce-scatter launch");
         }
-    }
-    for (u32 s = 0; s + 1 < N && what != kReduceScatter; ++s) {
-        a.step = s;
-        for (u64 c = 0; c < n_pieces; ++c) {
-            a.g.win_off = c * (n_pieces > 1 ? a.g.win_len : 0);
+        for (u32 s = 0; s + 1 < N && what != kReduceScatter; ++s) {
+            a.step = s;
             const hipError_t e = launch(nz_ring_step<T, kRingIters, true, REUSE>, blocks, a, st);
             if (e != hipSuccess) return hip_failed(e, "ring allgather launch");
         }
@@ -193,12 +194,22 @@ nz_status launch_ring_steps(RingArgs &a, u32 blocks, hipStream_t st, Collective 
     return NZ_OK;
 }
 
+// Bytes one launch stores: every node's piece (or whole segment) of every rail.
+u64 ring_launch_bytes(const RingArgs &a)
+{
+    u64 elems = 0;
+    for (u32 k = 0; k < a.g.n_rails; ++k) {
+        const u64 longest = a.g.q[k] + (a.g.rem[k] ? 1 : 0);
+        elems += (u64)a.g.n_nodes * std::min<u64>(longest, a.g.win_len);
+    }
+    return elems << a.elem_shift;
+}
+
 template <class T>
 nz_status launch_ring(RingArgs &a, u32 blocks, hipStream_t st, Collective what, u64 n_pieces)
 {
-    const u64 step_bytes = (a.g.off[a.g.n_rails] - a.g.off[0]) << a.elem_shift;
-    return step_bytes <= kRingReuseBytes ? launch_ring_steps<T, true>(a, blocks, st, what, n_pieces)
-                                         : launch_ring_steps<T, false>(a, blocks, st, what, n_pieces);
+    return ring_launch_bytes(a) <= kRingReuseBytes ? launch_ring_steps<T, true>(a, blocks, st, what, n_pieces)
+                                                   : launch_ring_steps<T, false>(a, blocks, st, what, n_pieces);
 }
 
 template <class T>
