@@ -24,7 +24,11 @@
  * sums are taken in fp64, left to right over the node index.
  *
  * Every function here is pinned by tests/test_oracle_*.py against closed
- * forms, brute force, hand-worked cases and library routines.
+ * forms, brute force, hand-worked cases and library routines.  For the data
+ * allocation scheme (Sec. 4.3) the oracle holds the definitions -- Eq. 4,
+ * Eq. 5, the minimum of Eq. 5 over the shares, the threshold of Eq. 6 -- and
+ * one subgradient reading of Eq. 7 / Eq. 8 (orc_balance_iterate); the
+ * library's own iteration is judged against the definitions.
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -572,6 +576,82 @@ double orc_balance_iterate(uint32_t n_rails, const double *t_setup, const double
     }
     for (uint32_t i = 0; i < R; ++i) alpha[i] = best_a[i];
     return best_t;
+}
+
+/*
+ * The definition the iteration aims at: the smallest value Eq. 5 can take
+ * over all shares alpha >= 0 that sum to one (rails given nothing sit out),
+ * found without any step rule.
+ *
+ * If the allreduce is to end by time T, rail i can carry at most
+ * (T - T_setup_i) * B_i bytes (nothing if T <= T_setup_i).  The capacity
+ *   cap(T) = sum_i max(0, (T - T_setup_i) * B_i)
+ * grows with T, and S bytes can be finished by time T exactly when
+ * cap(T) >= S.  The minimum of Eq. 5 is therefore the T with cap(T) = S,
+ * located here by plain bisection; the shares that reach it give each rail
+ * what it can carry by then, alpha_i = max(0, (T - T_setup_i) * B_i) / S.
+ * Returns T; alpha (may be NULL) receives the shares.  S > 0.
+ */
+static double capacity_by(uint32_t n_rails, const double *t_setup, const double *bw, double T)
+{
+    double cap = 0.0;
+    for (uint32_t i = 0; i < n_rails; ++i)
+        if (T > t_setup[i]) cap += (T - t_setup[i]) * bw[i];
+    return cap;
+}
+
+double orc_balance_optimum(uint32_t n_rails, const double *t_setup, const double *bw, double S,
+                           double *alpha)
+{
+    if (n_rails == 0 || !(S > 0.0)) return -1.0;
+    /* cap(lo) = 0 < S at the smallest startup latency; the best single rail's
+     * finishing time (Eq. 4) is certainly enough. */
+    double lo = t_setup[0];
+    for (uint32_t i = 1; i < n_rails; ++i)
+        if (t_setup[i] < lo) lo = t_setup[i];
+    double hi = orc_t_cold(n_rails, t_setup, bw, S, NULL);
+    for (int it = 0; it < 200; ++it) {
+        double mid = 0.5 * (lo + hi);
+        if (capacity_by(n_rails, t_setup, bw, mid) < S) lo = mid; else hi = mid;
+    }
+    if (alpha)
+        for (uint32_t i = 0; i < n_rails; ++i)
+            alpha[i] = hi > t_setup[i] ? (hi - t_setup[i]) * bw[i] / S : 0.0;
+    return hi;
+}
+
+/*
+ * Eq. 6: the message size at which cold start (Eq. 4) and hot start with its
+ * best shares (the minimum of Eq. 5) take the same time.  Sharing can never
+ * be slower than the best single rail, so T_cold(S) - T_hot(S) is zero up to
+ * the threshold and positive beyond it; the threshold is the largest S at
+ * which the two are still equal.  Bisection on S.  "Equal" means a relative
+ * difference of at most 1e-12 (the accuracy of the inner bisection).
+ * Returns HUGE_VAL when no size up to 1e30 bytes makes sharing pay (a single
+ * rail).
+ */
+static int sharing_pays(uint32_t n_rails, const double *t_setup, const double *bw, double S)
+{
+    double cold = orc_t_cold(n_rails, t_setup, bw, S, NULL);
+    double hot = orc_balance_optimum(n_rails, t_setup, bw, S, NULL);
+    return cold - hot > 1e-12 * cold;
+}
+
+double orc_threshold(uint32_t n_rails, const double *t_setup, const double *bw)
+{
+    if (n_rails == 0) return -1.0;
+    double hi = 1.0;
+    while (!sharing_pays(n_rails, t_setup, bw, hi)) {
+        hi *= 2.0;
+        if (hi > 1e30) return HUGE_VAL;
+    }
+    double lo = 0.0;   /* at S -> 0 everything goes to the rail that starts first */
+    for (int it = 0; it < 200; ++it) {
+        double mid = 0.5 * (lo + hi);
+        if (mid <= 0.0) break;
+        if (sharing_pays(n_rails, t_setup, bw, mid)) hi = mid; else lo = mid;
+    }
+    return lo;
 }
 
 /* ---------------------------------------------------------------------- */

@@ -28,7 +28,7 @@ __all__ = [
     "F32", "BF16", "F16", "I32", "ELEM_BYTES", "build", "threads",
     "rail_partition", "segment_map", "sum_float", "sum_i32", "round_to_storage",
     "ring_allreduce", "ring_allgather", "ring_allreduce_chunked", "failover_target", "pack", "unpack",
-    "t_cold", "t_hot", "balance_iterate", "net_efficiency", "efficiency_ratio",
+    "t_cold", "t_hot", "balance_iterate", "balance_optimum", "threshold", "net_efficiency", "efficiency_ratio",
     "bf16_to_f32", "f32_to_bf16", "f16_to_f32", "f32_to_f16", "storage_dtype",
 ]
 
@@ -67,6 +67,10 @@ def _L():
         lib.orc_t_hot.restype = dbl
         lib.orc_balance_iterate.argtypes = [u32, vp, vp, dbl, u32, vp]
         lib.orc_balance_iterate.restype = dbl
+        lib.orc_balance_optimum.argtypes = [u32, vp, vp, dbl, vp]
+        lib.orc_balance_optimum.restype = dbl
+        lib.orc_threshold.argtypes = [u32, vp, vp]
+        lib.orc_threshold.restype = dbl
         lib.orc_net_efficiency.argtypes = [dbl, dbl, dbl]
         lib.orc_net_efficiency.restype = dbl
         lib.orc_efficiency_ratio.argtypes = [dbl] * 6
@@ -265,6 +269,27 @@ def balance_iterate(t_setup, bw, S: float, iterations: int = 20000) -> Tuple[np.
     if t < 0:
         raise ValueError("oracle: balance_iterate: invalid argument")
     return a, float(t)
+
+
+def balance_optimum(t_setup, bw, S: float) -> Tuple[np.ndarray, float]:
+    """The minimum of Eq. 5 over all shares (bisection on the finishing time); returns
+    (shares, that minimum)."""
+    ts, b = _model(t_setup, bw)
+    a = np.zeros(len(ts), dtype=np.float64)
+    t = _L().orc_balance_optimum(len(ts), ts.ctypes.data, b.ctypes.data, float(S), a.ctypes.data)
+    if t < 0:
+        raise ValueError("oracle: balance_optimum: invalid argument")
+    return a, float(t)
+
+
+def threshold(t_setup, bw) -> float:
+    """Eq. 6: the largest message size at which cold start and the best hot start take the
+    same time (infinity if sharing never pays)."""
+    ts, b = _model(t_setup, bw)
+    t = _L().orc_threshold(len(ts), ts.ctypes.data, b.ctypes.data)
+    if t < 0:
+        raise ValueError("oracle: threshold: invalid argument")
+    return float(t)
 
 
 def net_efficiency(t_setup: float, bw: float, S: float) -> float:

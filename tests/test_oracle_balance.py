@@ -57,6 +57,113 @@ def test_iteration_reaches_the_brute_force_optimum(orc, ts, bw, S):
     assert t <= tc * (1 + 1e-12)                        # never worse than the best single rail
 
 
+def _zoom_best(orc, ts, bw, S, rounds=9, steps=20):
+    """Brute force over the simplex with Eq. 5 alone: a grid over the whole simplex (vertices and
+    faces included: rails given nothing sit out), then ever finer grids around the best point."""
+    R = len(ts)
+    best_t, best_a = np.inf, None
+    centre, width = np.full(R - 1, 0.5), 0.5
+    for _ in range(rounds):
+        axes = [np.unique(np.clip(np.linspace(c - width, c + width, steps + 1), 0.0, 1.0)) for c in centre]
+        for head in itertools.product(*axes):
+            last = 1.0 - sum(head)
+            if last < -1e-15:
+                continue
+            a = list(head) + [max(last, 0.0)]
+            t = orc.t_hot(ts, bw, S, a)
+            if t < best_t:
+                best_t, best_a = t, a
+        centre, width = np.array(best_a[:-1]), width * 2.5 / steps
+    return best_t, best_a
+
+
+_MODELS = [
+    ([1e-3, 4e-3], [1e9, 4e9], 8e6),
+    ([1e-3, 4e-3], [1e9, 4e9], 1e6),            # small: everything on rail 0
+    ([9e-6, 982e-6], [0.35e9, 0.2e9], 64e6),    # an RDMA-like and a TCP-like rail
+    ([1e-4, 1e-4, 1e-4], [1e9, 1e9, 1e9], 3e6),
+    ([1e-4, 2e-4, 5e-3], [1e9, 3e9, 2e9], 2e6),  # the third rail starts too late to help
+    ([3e-4, 1e-4, 2e-4], [2e9, 1e9, 5e8], 9e6),
+]
+
+
+@pytest.mark.parametrize("ts,bw,S", _MODELS)
+def test_optimum_is_the_brute_force_minimum_of_eq5(orc, ts, bw, S):
+    a, t = orc.balance_optimum(ts, bw, S)
+    assert a.sum() == pytest.approx(1.0, abs=1e-12) and (a >= 0).all()
+    assert orc.t_hot(ts, bw, S, a) == pytest.approx(t, rel=1e-12)       # the shares do reach it
+    tg, ag = _zoom_best(orc, ts, bw, S, steps=40 if len(ts) == 2 else 20)
+    assert t == pytest.approx(tg, rel=1e-6)
+    assert t <= tg * (1 + 1e-12)                                         # nothing on the grid beats it
+    assert np.abs(a - np.array(ag)).max() <= 1e-5
+
+
+def test_optimum_hand_cases_and_its_characterisation(orc):
+    # 8 MB over (1 ms, 1 GB/s) and (4 ms, 4 GB/s): 1 + 8a = 4 + 2(1 - a) ms -> a = 1/2, T = 5 ms
+    a, t = orc.balance_optimum([1e-3, 4e-3], [1e9, 4e9], 8e6)
+    assert np.allclose(a, [0.5, 0.5], atol=1e-12) and t == pytest.approx(5e-3, rel=1e-12)
+    # equal startup latencies: shares proportional to bandwidth, T = T_setup + S / sum B
+    a, t = orc.balance_optimum([2e-4] * 3, [1e9, 2e9, 5e9], 4e7)
+    assert np.allclose(a, np.array([1, 2, 5]) / 8, atol=1e-12) and t == pytest.approx(2e-4 + 4e7 / 8e9, rel=1e-12)
+    # homogeneous rails share equally
+    a, _ = orc.balance_optimum([2e-4] * 4, [1e9] * 4, 16e6)
+    assert np.allclose(a, 0.25, atol=1e-12)
+    # a message the first rail finishes before the second could start stays on the first
+    a, t = orc.balance_optimum([1e-3, 4e-3], [1e9, 4e9], 1e6)
+    assert list(a) == [1.0, 0.0] and t == pytest.approx(2e-3, rel=1e-12)
+    # what characterises the minimum of a maximum: rails that take part finish together, the
+    # others could not even have started by then
+    rng = np.random.default_rng(11)
+    for _ in range(200):
+        R = int(rng.integers(1, 9))
+        ts, bw, S = 10 ** rng.uniform(-6, -2, R), 10 ** rng.uniform(7, 10.5, R), 10 ** rng.uniform(3, 9.5)
+        a, t = orc.balance_optimum(ts, bw, S)
+        assert a.sum() == pytest.approx(1.0, abs=1e-9)
+        for i in range(R):
+            if a[i] > 0:
+                assert ts[i] + a[i] * S / bw[i] == pytest.approx(t, rel=1e-9)
+            else:
+                assert ts[i] >= t * (1 - 1e-12)
+        assert t <= orc.t_cold(ts, bw, S)[0] * (1 + 1e-12)
+        # any other allocation is no better: perturb the shares
+        for _ in range(5):
+            b = np.clip(a + rng.normal(0, 0.05, R), 0, None)
+            if b.sum() > 0:
+                assert orc.t_hot(ts, bw, S, b / b.sum()) >= t * (1 - 1e-9)
+
+
+def test_eq6_threshold_by_hand_and_by_its_definition(orc):
+    # (4 ms - 1 ms) * 1 GB/s = 3 MB: up to there the first rail is done before the second starts
+    assert orc.threshold([1e-3, 4e-3], [1e9, 4e9]) == pytest.approx(3e6, rel=1e-9)
+    assert orc.threshold([1e-3], [1e9]) == float("inf")
+    assert orc.threshold([1e-3, 1e-3], [1e9, 2e9]) == pytest.approx(0.0, abs=1e-3)   # equal start: always share
+    rng = np.random.default_rng(12)
+    for _ in range(100):
+        R = int(rng.integers(2, 7))
+        ts, bw = 10 ** rng.uniform(-6, -2, R), 10 ** rng.uniform(7, 10.5, R)
+        th = orc.threshold(ts, bw)
+        # Eq. 6 holds at the threshold and below it, and fails above it
+        for S, equal in ((0.5 * th, True), (th, True), (1.01 * th + 1.0, False)):
+            if S > 0:
+                cold, hot = orc.t_cold(ts, bw, S)[0], orc.balance_optimum(ts, bw, S)[1]
+                assert (hot == pytest.approx(cold, rel=1e-11)) == equal, (S, th)
+                assert hot <= cold * (1 + 1e-12)
+    # the paper's Table 1 rails (fitted as in the Eq. 5 test): 1 KB lies below the threshold (no
+    # split helps there), 8 MB and 64 MB above it (the 1:1 split beats both single rails)
+    tab = _table1()
+    small, large = min(tab), max(tab)
+
+    def fit(col):
+        t1, t2 = tab[small][col] * 1e-6, tab[large][col] * 1e-6
+        b = (large - small) / (t2 - t1)
+        return t1 - small / b, b
+
+    (ts_s, b_s), (ts_t, b_t) = fit(0), fit(1)
+    th = orc.threshold([ts_t, ts_s], [b_t, b_s])
+    for S, row in tab.items():
+        assert (S > th) == (row[2] < min(row[0], row[1])), (S, th)
+
+
 def test_homogeneous_rails_share_equally_and_bandwidth_proportional(orc):
     a, _ = orc.balance_iterate([2e-4] * 4, [1e9] * 4, 16e6)
     assert np.allclose(a, 0.25, atol=2e-3)
