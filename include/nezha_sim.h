@@ -174,8 +174,8 @@ nz_status nz_allgather_sim(void *const *bufs, uint32_t n_nodes, uint64_t n_elems
                            void *stream);
 
 /*
- * Ring_Chunked allreduce.  (Evaluation, GPT-3 scalability: the Ring_Chunked
- * algorithm splits large data packets and pipelines their transmission.)
+ * Ring_Chunked allreduce.  (Evaluation, GPT-3 scalability experiment: the
+ * chunked variant of the ring named there.)
  *
  * The ring of NZ_RING_STEPWISE with every segment transfer cut into pieces of
  * at most chunk_elems elements (> 0): each of the 2 (N - 1) steps is issued as
@@ -240,6 +240,23 @@ nz_status nz_allreduce_sim_failover(const void *const *node_bufs, uint32_t n_nod
  *   hot        (may be NULL): 1 in the hot-start state, 0 in cold start.
  * nz_balance_threshold: the message size (bytes) up to which the state is
  * cold (infinity for a single rail).
+ *
+ * nz_balance_iterate: the shares by the paper's own method, for
+ * msg_bytes > 0.  Start: Eq. 8, alpha_i = (T - T_i) / (T (R - 1)) with T_i
+ * rail i's latency under a uniform split of the message, T their sum and R
+ * the number of rails.  Step (Eq. 7): the derivative of T_hot is S / B_w on
+ * the slowest rail w that takes part and zero elsewhere, so a step takes a
+ * share from w; the share goes to the rail f that would finish first (a
+ * rail holding nothing counts with its startup latency), and the step
+ * length is the exact line search along that direction: w and f finish
+ * together; if w's startup latency alone reaches that common time, w hands
+ * over all it has and sits out.  The iteration ends when no rail would finish
+ * before the slowest one, when a step would move less than half a unit of
+ * the data-length table (2^-21 of the message), or after max_iterations
+ * steps.  T_hot never rises from one step to the next.  alpha, ratios, t_hot
+ * as for nz_balance (each may be NULL); iterations (may be NULL) receives the
+ * number of steps taken.  No cold/hot decision is made here: compare t_hot
+ * with nz_balance's t_cold.
  */
 #define NZ_RATIO_SCALE (1u << 20)
 
@@ -253,6 +270,10 @@ nz_status nz_balance(const nz_rail_model *rails, uint32_t n_rails, double msg_by
 
 nz_status nz_balance_threshold(const nz_rail_model *rails, uint32_t n_rails,
                                double *threshold_bytes);
+
+nz_status nz_balance_iterate(const nz_rail_model *rails, uint32_t n_rails, double msg_bytes,
+                             uint32_t max_iterations, double *alpha, uint32_t *ratios,
+                             double *t_hot, uint32_t *iterations);
 
 /*
  * Network efficiency and the real-time efficiency ratio.  (Sec. 2.1.2, Eq. 2:

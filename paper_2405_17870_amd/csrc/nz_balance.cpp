@@ -7,11 +7,13 @@
 // at the threshold size (Eq. 6); the shares are refined by descent on the hot
 // latency (Eq. 7) from latency-derived starting shares (Eq. 8).
 //
-// With the rails' (T_setup, B) given, the point that descent converges to can
-// be written down directly: the slowest-rail latency is minimal when every
-// rail that takes part finishes at the same time T and every rail whose
-// startup latency alone exceeds T sits out ("water filling" over the startup
-// latencies).  That closed form is what is computed here; no iteration.
+// Two routes to the shares are offered.  nz_balance_iterate is the paper's
+// method: Eq. 8 starting shares, then steps of Eq. 7 until the data-length
+// table no longer changes.  nz_balance writes down the point that descent
+// converges to directly: the slowest-rail latency is minimal when every rail
+// that takes part finishes at the same time T and every rail whose startup
+// latency alone exceeds T sits out ("water filling" over the startup
+// latencies); no iteration.
 //
 // Sec. 2.1.2 Eq. 2 (network efficiency) and Sec. 2.2.1 Eq. 3 (the real-time
 // efficiency ratio that gates splitting) are evaluated at the end of the file.
@@ -43,6 +45,42 @@ std::vector<uint32_t> by_setup(const nz_rail_model *rails, uint32_t n_rails)
     std::stable_sort(order.begin(), order.end(),
                      [&](uint32_t x, uint32_t y) { return rails[x].setup_s < rails[y].setup_s; });
     return order;
+}
+
+// Integer weights that sum to exactly NZ_RATIO_SCALE: floors, then the leftover
+// units to the largest remainders (lowest index among equals).
+void shares_to_ratios(const double *share, uint32_t n_rails, uint32_t *ratios)
+{
+    const uint32_t total = NZ_RATIO_SCALE;
+    double frac[NZ_MAX_RAILS];
+    uint32_t given = 0;
+    for (uint32_t i = 0; i < n_rails; ++i) {
+        const double x = share[i] * total;
+        double fl = std::floor(x);
+        if (fl > total) fl = total;
+        ratios[i] = (uint32_t)fl;
+        frac[i] = x - fl;
+        given += ratios[i];
+    }
+    while (given < total) {
+        uint32_t pick = 0;
+        for (uint32_t i = 1; i < n_rails; ++i)
+            if (frac[i] > frac[pick]) pick = i;
+        ratios[pick] += 1;
+        frac[pick] = -1.0;
+        ++given;
+        bool any = false;
+        for (uint32_t i = 0; i < n_rails; ++i) any = any || frac[i] >= 0.0;
+        if (!any)
+            for (uint32_t i = 0; i < n_rails; ++i) frac[i] = 0.0;
+    }
+    while (given > total) {  // only through floating-point excess in the shares
+        uint32_t pick = 0;
+        for (uint32_t i = 1; i < n_rails; ++i)
+            if (ratios[i] > ratios[pick]) pick = i;
+        ratios[pick] -= 1;
+        --given;
+    }
 }
 
 }  // namespace
@@ -95,44 +133,76 @@ nz_status nz_balance(const nz_rail_model *rails, uint32_t n_rails, double msg_by
     }
 
     if (alpha) std::copy(share.begin(), share.end(), alpha);
-    if (ratios) {
-        // Integer weights that sum to exactly 2^20: floors, then the leftover
-        // units to the largest remainders (lowest index among equals).
-        const uint32_t total = NZ_RATIO_SCALE;
-        std::vector<double> frac(n_rails);
-        uint32_t given = 0;
-        for (uint32_t i = 0; i < n_rails; ++i) {
-            const double x = share[i] * total;
-            double fl = std::floor(x);
-            if (fl > total) fl = total;
-            ratios[i] = (uint32_t)fl;
-            frac[i] = x - fl;
-            given += ratios[i];
-        }
-        while (given < total) {
-            uint32_t pick = 0;
-            for (uint32_t i = 1; i < n_rails; ++i)
-                if (frac[i] > frac[pick]) pick = i;
-            ratios[pick] += 1;
-            frac[pick] = -1.0;
-            ++given;
-            bool any = false;
-            for (uint32_t i = 0; i < n_rails; ++i) any = any || frac[i] >= 0.0;
-            if (!any)
-                for (uint32_t i = 0; i < n_rails; ++i) frac[i] = 0.0;
-        }
-        while (given > total) {  // only through floating-point excess in the shares
-            uint32_t pick = 0;
-            for (uint32_t i = 1; i < n_rails; ++i)
-                if (ratios[i] > ratios[pick]) pick = i;
-            ratios[pick] -= 1;
-            --given;
-        }
-    }
+    if (ratios) shares_to_ratios(share.data(), n_rails, ratios);
     if (t_cold) *t_cold = cold;
     if (t_hot) *t_hot = is_hot ? level : cold;
     if (best_rail) *best_rail = best;
     if (hot) *hot = is_hot ? 1 : 0;
+    return NZ_OK;
+}
+
+nz_status nz_balance_iterate(const nz_rail_model *rails, uint32_t n_rails, double msg_bytes,
+                             uint32_t max_iterations, double *alpha, uint32_t *ratios, double *t_hot,
+                             uint32_t *iterations)
+{
+    if (n_rails > NZ_MAX_RAILS) return NZ_ERR_UNSUPPORTED;
+    if (!valid_model(rails, n_rails) || !(msg_bytes > 0.0) || !std::isfinite(msg_bytes))
+        return NZ_ERR_INVALID_ARG;
+    const uint32_t R = n_rails;
+    const double S = msg_bytes;
+    double a[NZ_MAX_RAILS], t[NZ_MAX_RAILS];
+
+    // Eq. 8: each rail's latency T_i under a uniform split, T their sum; a
+    // rail that is slow under the uniform split starts with a smaller share.
+    if (R == 1) {
+        a[0] = 1.0;
+    } else {
+        double total = 0.0;
+        for (uint32_t i = 0; i < R; ++i) {
+            t[i] = rails[i].setup_s + (S / R) / rails[i].bytes_per_s;
+            total += t[i];
+        }
+        for (uint32_t i = 0; i < R; ++i) a[i] = (total - t[i]) / (total * (double)(R - 1));
+    }
+
+    // Eq. 7.  T_hot is the maximum over the rails that take part, so its
+    // derivative is S / B on the slowest of them and zero elsewhere: a step
+    // takes a share from the slowest rail.  The share goes to the rail that
+    // would finish first (of all ways to keep the sum at one, the one that
+    // raises T_hot least), and its size is the exact line search along that
+    // direction: the two rails finish together.  A rail whose startup latency
+    // alone reaches that common time hands over all it has and sits out.
+    const double table_unit = 1.0 / (2.0 * NZ_RATIO_SCALE);  // half a unit of the data-length table
+    uint32_t k = 0;
+    for (; k < max_iterations && R > 1; ++k) {
+        uint32_t w = R, f = R;
+        for (uint32_t i = 0; i < R; ++i) {
+            t[i] = rails[i].setup_s + a[i] * S / rails[i].bytes_per_s;
+            if (a[i] > 0.0 && (w == R || t[i] > t[w])) w = i;
+        }
+        for (uint32_t i = 0; i < R; ++i)
+            if (i != w && (f == R || t[i] < t[f])) f = i;
+        if (!(t[f] < t[w])) break;  // nobody could take anything off the slowest rail
+        const double bw = rails[w].bytes_per_s, bf = rails[f].bytes_per_s;
+        const double meet = (bw * t[w] + bf * t[f]) / (bw + bf);
+        if (rails[w].setup_s >= meet) {
+            a[f] += a[w];
+            a[w] = 0.0;
+            continue;
+        }
+        const double delta = (t[w] - meet) * bw / S;
+        if (delta < table_unit) break;  // the data-length table has converged
+        a[w] -= delta;
+        a[f] += delta;
+    }
+
+    double slowest = 0.0;
+    for (uint32_t i = 0; i < R; ++i)
+        if (a[i] > 0.0) slowest = std::max(slowest, rails[i].setup_s + a[i] * S / rails[i].bytes_per_s);
+    if (alpha) std::copy(a, a + R, alpha);
+    if (ratios) shares_to_ratios(a, R, ratios);
+    if (t_hot) *t_hot = slowest;
+    if (iterations) *iterations = k;
     return NZ_OK;
 }
 

@@ -34,6 +34,7 @@ EXPORTS = [
     "nz_rail_partition_ex", "nz_segment_map", "nz_allreduce_sim", "nz_reduce_scatter_sim",
     "nz_allgather_sim", "nz_allreduce_sim_chunked", "nz_failover_target",
     "nz_allreduce_sim_failover", "nz_pack", "nz_unpack", "nz_balance", "nz_balance_threshold",
+    "nz_balance_iterate",
     "nz_net_efficiency", "nz_efficiency_ratio",
 ]
 
@@ -87,6 +88,8 @@ def load() -> ctypes.CDLL:
     lib.nz_balance.restype = i32
     lib.nz_balance_threshold.argtypes = [vp, u32, vp]
     lib.nz_balance_threshold.restype = i32
+    lib.nz_balance_iterate.argtypes = [vp, u32, ctypes.c_double, u32, vp, vp, vp, vp]
+    lib.nz_balance_iterate.restype = i32
     lib.nz_net_efficiency.argtypes = [vp, ctypes.c_double, vp]
     lib.nz_net_efficiency.restype = i32
     lib.nz_efficiency_ratio.argtypes = [vp, u32, ctypes.c_double, vp, vp]
@@ -288,6 +291,21 @@ def nz_balance_threshold(setup_s: Sequence[float], bytes_per_s: Sequence[float])
     out = ctypes.c_double(0)
     _check(lib.nz_balance_threshold(_models(setup_s, bytes_per_s), len(setup_s), ctypes.byref(out)))
     return out.value
+
+
+def nz_balance_iterate(setup_s: Sequence[float], bytes_per_s: Sequence[float], msg_bytes: float,
+                       max_iterations: int = 100) -> dict:
+    """The shares by the paper's iteration (Sec. 4.3): Eq. 8 start, then steps of Eq. 7 until the
+    data-length table has converged.  Host only.  Returns alpha, ratios, t_hot, iterations."""
+    lib = load()
+    R = len(setup_s)
+    alpha = np.zeros(max(R, 1), dtype=np.float64)
+    ratios = np.zeros(max(R, 1), dtype=np.uint32)
+    th, it = ctypes.c_double(0), ctypes.c_uint32(0)
+    _check(lib.nz_balance_iterate(_models(setup_s, bytes_per_s), R, float(msg_bytes),
+                                  int(max_iterations), alpha.ctypes.data, ratios.ctypes.data,
+                                  ctypes.byref(th), ctypes.byref(it)))
+    return {"alpha": alpha[:R], "ratios": ratios[:R], "t_hot": th.value, "iterations": int(it.value)}
 
 
 NZ_TOLERANCE_TAU = 5.0
