@@ -105,16 +105,22 @@ def check_fused_against_oracle(orc, dtype: str, got: np.ndarray, host_ins: Seque
         assert (err <= bound).all(), f"{label}: fp32 error exceeds 1e-6*sum|x| by {worst}"
         return 0
     want = orc.round_to_storage(ORC_CODE[dtype], s)
-    nan_w, nan_g = is_nan16(want, dtype), is_nan16(got, dtype)
+    # Elements whose bits agree need no further look; the rest (typically well under 1 %) go
+    # through the ulp rule.
+    diff = np.flatnonzero(got != want)
+    if diff.size == 0:
+        return 0
+    g_d, w_d, s_d, a_d = got[diff], want[diff], s[diff], a[diff]
+    nan_w, nan_g = is_nan16(w_d, dtype), is_nan16(g_d, dtype)
     assert np.array_equal(nan_w, nan_g), f"{label}: NaN placement differs"
     ok = ~nan_w
-    dist = np.abs(monotone(got[ok]) - monotone(want[ok]))
+    dist = np.abs(monotone(g_d[ok]) - monotone(w_d[ok]))
     far = dist > 1
     if far.any():
-        g = half_to_f64(got[ok][far], dtype)
+        g = half_to_f64(g_d[ok][far], dtype)
         eps = 2.0 ** -8 if dtype == "bf16" else 2.0 ** -11      # half an ulp, relative
-        bound = FP32_REL * a[ok][far] + eps * np.abs(g)
-        assert (np.abs(g - s[ok][far]) <= bound).all(), \
+        bound = FP32_REL * a_d[ok][far] + eps * np.abs(g)
+        assert (np.abs(g - s_d[ok][far]) <= bound).all(), \
             f"{label}: {dtype} result more than 1 ulp away and outside the fp32 bound"
     return int(far.sum())
 
