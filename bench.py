@@ -43,15 +43,17 @@ def parse_args():
                         "rs, ag = fused reduce-scatter-only / allgather-only; chunked = Ring_Chunked; "
                         "failover = fused allreduce with the last rail failing; "
                         "packed = fused allreduce, in place, of every rail's contiguous send buffers "
-                        "(the route pack -> allreduce -> unpack; put it between pack and unpack)")
+                        "(the route pack -> allreduce -> unpack; put it between pack and unpack); "
+                        "packed_out = the same allreduce from the send buffers into separate result "
+                        "buffers (out of place; unpack_out then unpacks from those)")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--placement", default="spread", choices=["spread", "packed", "torch"],
                    help="where the buffers live in HBM: spread = inputs in the first 96 GiB region, "
                         "written buffers striped over all three regions (default); packed = all in the "
                         "first region; torch = plain torch allocations")
-    p.add_argument("--reference-one-region", action="store_true",
-                   help="after the timed steps, also time the fused call with its outputs placed in "
-                        "the inputs' HBM region (reported as fused_with_outputs_in_one_region)")
+    p.add_argument("--no-plain", action="store_true",
+                   help="skip the second measurement of every part on plain torch allocations "
+                        "(reported as plain_allocations when the timed placement is another one)")
     p.add_argument("--packed-offset-gib", type=float, default=0.0,
                    help="with --placement packed: arena offset at which the buffers start")
     p.add_argument("--chunk-elems", type=int, default=1 << 20,
@@ -101,9 +103,25 @@ def device_facts(torch):
     return facts
 
 
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(w, n_sample: int, parts):
-    """The oracle, as it stands, on a bounded slice of the same workload (same node count,
-    same ratios, n_sample elements per node)."""
+    """The oracle, as it stands, on a bounded slice of the same workload (same node count, same
+    ratios, the first n_sample elements of every node).  Every leg is reported on its own, in
+    algorithmic bytes per second of what that leg does:
+      sum, one thread / all threads ... the definitional N-way sum + rounding to the storage
+          type: N reads and one result written per element, (N + 1) * S;
+      ring, one thread ... the literal ring, 5 (N - 1) * S;
+      pack and unpack, one thread ... 2 * S each per node and rail.
+    `value` is the all-threads definitional sum."""
     import numpy as np
     import oracle as orc
     from paper_2405_17870_amd import inputs
@@ -115,37 +133,58 @@ def cpu_baseline(w, n_sample: int, parts):
     host = [inputs.to_host_storage(t) for t in inputs.workload_buffers(w, device="cpu", n_elems=n)]
     S = n * e
     seg = orc.segment_map(orc.rail_partition(n, w.ratios, e), N)
-    bytes_done = 0
-    t0 = time.perf_counter()
-    for p in ("fused", "packed"):        # the packed route sums the same values once more
-        if p not in parts:
-            continue
+    all_threads = orc.threads()
+
+    def definitional_sum(bufs):
         if w.dtype == "i32":
-            orc.sum_i32(host)
+            orc.sum_i32(bufs)
         else:
-            s, _ = orc.sum_float(code, host)
+            s, _ = orc.sum_float(code, bufs)
             orc.round_to_storage(code, s)
-        bytes_done += 2 * N * S
+
+    legs = {}
+    t_all = time.perf_counter()
+    t0 = time.perf_counter()
+    definitional_sum(host)
+    dt = time.perf_counter() - t0
+    legs["sum_all_threads"] = {"GBps": round((N + 1) * S / dt / 1e9, 3), "seconds": round(dt, 3),
+                               "threads": all_threads, "elems_per_node": n}
+    n1 = max(n // 8, 1)                                  # one thread is slow: an eighth of the slice
+    orc.set_threads(1)
+    try:
+        t0 = time.perf_counter()
+        definitional_sum([h[:n1] for h in host])
+        dt = time.perf_counter() - t0
+    finally:
+        orc.set_threads(all_threads)
+    legs["sum_one_thread"] = {"GBps": round((N + 1) * n1 * e / dt / 1e9, 3), "seconds": round(dt, 3),
+                              "threads": 1, "elems_per_node": n1}
     if "ring" in parts:
+        t0 = time.perf_counter()
         orc.ring_allreduce(code, host, seg)
-        bytes_done += 5 * (N - 1) * S
+        dt = time.perf_counter() - t0
+        legs["ring_one_thread"] = {"GBps": round(5 * (N - 1) * S / dt / 1e9, 3), "seconds": round(dt, 3),
+                                   "threads": 1, "elems_per_node": n}
     if "pack" in parts or "unpack" in parts:
         ids = list(range(N))
+        moved = 0
+        t0 = time.perf_counter()
         for rail in range(len(w.ratios)):
             for m in range(N):
                 buf, _ = orc.pack(host[m], seg, rail, ids, e)
-                if "pack" in parts:
-                    bytes_done += 2 * buf.size
-                if "unpack" in parts:
-                    orc.unpack(buf, seg, rail, ids, e, host[m])
-                    bytes_done += 2 * buf.size
-    dt = time.perf_counter() - t0
+                orc.unpack(buf, seg, rail, ids, e, host[m])
+                moved += 4 * buf.size
+        dt = time.perf_counter() - t0
+        legs["pack_unpack_one_thread"] = {"GBps": round(moved / dt / 1e9, 3), "seconds": round(dt, 3),
+                                          "threads": 1, "elems_per_node": n}
+    total = time.perf_counter() - t_all
     return {
-        "value": round(bytes_done / dt / 1e9, 3), "unit": "GB/s", "cores": orc.threads(),
-        "kind": "oracle", "seconds": round(dt, 3),
-        "sample": (f"same step ({'+'.join(parts)}) on the first {n} elements of each of the "
-                   f"{N} nodes of {w.name}; the definitional sum runs on {orc.threads()} OpenMP "
-                   "threads, the ring emulation and pack/unpack on one"),
+        "value": legs["sum_all_threads"]["GBps"], "unit": "GB/s", "cores": all_threads,
+        "kind": "oracle", "seconds": round(total, 3), "cpu": cpu_model(),
+        "hardware_threads": os.cpu_count(), "legs": legs,
+        "sample": (f"the first {n} elements of each of the {N} nodes of {w.name}; value = the oracle's "
+                   f"definitional {N}-way sum and rounding on {all_threads} OpenMP threads, "
+                   f"({N} + 1) * S bytes over its time; the other legs (one thread) are listed under legs"),
     }
 
 
@@ -238,51 +277,58 @@ def main() -> int:
     tdtype = inputs.TORCH_DTYPE[w.dtype]
     rail_off = nz.nz_rail_partition(n, e, w.ratios)
     seg = nz.nz_segment_map(rail_off, N)
-    need_send = any(p in parts for p in ("pack", "unpack", "packed"))
+    need_send = any(p in parts for p in ("pack", "unpack", "packed", "packed_out", "unpack_out"))
+    need_result = any(p in parts for p in ("packed_out", "unpack_out"))
     rail_len = [max(int(rail_off[k + 1] - rail_off[k]), 1) for k in range(R)]
-    placement_note = "plain torch allocations"
-    arena = placement.try_arena(dev) if args.placement != "torch" else None
-    packed_ref_outs = None
-    if arena is not None:
-        written = (0, 1, 2) if args.placement == "spread" else (0,)
-        if args.placement == "packed" and args.packed_offset_gib > 0:
-            arena.set_cursor(0, int(args.packed_offset_gib * (1 << 30)))
-        ins = [arena.alloc(n, tdtype, 0) for _ in range(N)]
-        outs = arena.alloc_striped(N, n, tdtype, written)
-        send = [arena.alloc_striped(N, rail_len[k], tdtype, written, start=k + 1) for k in range(R)] \
-            if need_send else []
-        if args.reference_one_region and args.placement == "spread" and "fused" in parts and arena.free_in(0) >= N * (n * e + (2 << 20)):
-            packed_ref_outs = [arena.alloc(n, tdtype, 0) for _ in range(N)]
-        placement_note = ("inputs in the first 96 GiB HBM region; outputs and send buffers striped over "
-                          "the three 96 GiB regions" if args.placement == "spread"
-                          else f"all buffers back to back from arena offset {args.packed_offset_gib:g} GiB")
+
+    def make_buffers(kind):
+        """Inputs (filled), outputs and per-rail send buffers under one of the placements."""
+        arena = placement.try_arena(dev) if kind != "torch" else None
+        if arena is None:
+            ins = inputs.workload_buffers(w, device=dev)
+            outs = [torch.empty_like(t) for t in ins]
+            send = [[torch.zeros(rail_len[k], dtype=tdtype, device=dev) for _ in range(N)] for k in range(R)] \
+                if need_send else []
+            if need_result:          # per-rail result buffers of the out-of-place packed route
+                send += [[torch.zeros(rail_len[k], dtype=tdtype, device=dev) for _ in range(N)] for k in range(R)]
+            return ins, outs, send, None, "plain torch allocations"
+        if kind == "packed":
+            arena.pack_from(int(args.packed_offset_gib * (1 << 30)))
+            note = f"all buffers back to back from arena offset {args.packed_offset_gib:g} GiB"
+        else:
+            note = ("one arena over HBM, offsets from nz_hbm_place: inputs together in the first 96 GiB "
+                    "region, outputs and send buffers spread over the three regions")
+        ins = arena.alloc_together(N, n, tdtype, 0)
+        outs = arena.alloc_striped(N, n, tdtype, 0)
+        send = [arena.alloc_striped(N, rail_len[k], tdtype, k + 1) for k in range(R)] if need_send else []
+        if need_result:
+            send += [arena.alloc_striped(N, rail_len[k], tdtype, k + 2) for k in range(R)]
         for i in range(N):
             ins[i].copy_(inputs.node_buffer(w.dtype, n, w.seed, i, device=dev, std=w.std,
                                             outlier_frac=w.outlier_frac, outlier_scale=w.outlier_scale))
         for group in send:
             for t in group:
                 t.zero_()
-    else:
-        ins = inputs.workload_buffers(w, device=dev)
-        outs = [torch.empty_like(t) for t in ins]
-        send = [[torch.zeros(rail_len[k], dtype=tdtype, device=dev) for _ in range(N)] for k in range(R)] \
-            if need_send else []
+        return ins, outs, send, arena, note
+
+    ins, outs, send, arena, placement_note = make_buffers(args.placement)
     ids = list(range(N)) if args.pack_order == "rail" else [(N // 2 - s) % N for s in range(N)]
     torch.cuda.synchronize()
 
-    fused_outs = [outs[1]] * N if args.shared_output else outs
     K = 1 if args.shared_output else N
+    bufs = {"ins": ins, "outs": outs, "send": send}
     alg_bytes = {"fused": (N + K) * S, "ring": 5 * (N - 1) * S, "pack": 2 * N * S, "unpack": 2 * N * S,
                  # optional parts: the two halves on their own, fused form
                  "rs": (N + 1) * S, "ag": N * S,
                  # Ring_Chunked moves the ring's bytes in more launches; failover the fused bytes in two
                  "chunked": 5 * (N - 1) * S, "failover": 2 * N * S,
                  # every rail's N send buffers reduced in place: N reads + N writes of the payload
-                 "packed": 2 * N * S}
+                 "packed": 2 * N * S, "packed_out": 2 * N * S, "unpack_out": 2 * N * S}
 
     def run_part(p):
+        ins, outs, send = bufs["ins"], bufs["outs"], bufs["send"]
         if p == "fused":
-            nz.nz_allreduce_sim(ins, n, w.ratios, w.dtype, "fused", fused_outs)
+            nz.nz_allreduce_sim(ins, n, w.ratios, w.dtype, "fused", [outs[1]] * N if args.shared_output else outs)
         elif p == "ring":
             nz.nz_allreduce_sim(ins, n, w.ratios, w.dtype, "ring-stepwise", outs)
         elif p == "rs":
@@ -297,6 +343,13 @@ def main() -> int:
             for k in range(R):
                 if rail_off[k + 1] > rail_off[k]:
                     nz.nz_allreduce_sim(send[k], int(rail_off[k + 1] - rail_off[k]), (1,), w.dtype, "fused", send[k])
+        elif p == "packed_out":
+            for k in range(R):
+                if rail_off[k + 1] > rail_off[k]:
+                    nz.nz_allreduce_sim(send[k], int(rail_off[k + 1] - rail_off[k]), (1,), w.dtype, "fused", send[R + k])
+        elif p == "unpack_out":
+            for k in range(R):
+                nz.nz_unpack(send[R + k], seg, k, ids, e, outs)
         elif p == "pack":
             for k in range(R):
                 nz.nz_pack(ins, seg, k, ids, e, send[k], send[k][0].numel() * e)
@@ -305,6 +358,25 @@ def main() -> int:
                 nz.nz_unpack(send[k], seg, k, ids, e, outs)
         else:
             raise SystemExit(f"unknown part {p!r}")
+
+    def time_parts(reps, warm):
+        """Mean time of every part on its own (HIP events on the launch stream)."""
+        res = {}
+        for p in parts:
+            for _ in range(warm):
+                run_part(p)
+            ev = []
+            for _ in range(reps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                run_part(p)
+                b.record()
+                ev.append((a, b))
+            torch.cuda.synchronize()
+            ms = sum(a.elapsed_time(b) for a, b in ev) / len(ev)
+            gbs = alg_bytes[p] / (ms * 1e-3) / 1e9
+            res[p] = {"ms": round(ms, 4), "hbm_GBps": round(gbs, 1), "frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}
+        return res
 
     def step(events=None):
         for p in parts:
@@ -360,17 +432,20 @@ def main() -> int:
                          "algorithmic_bytes": alg_bytes[p]}
 
     head = "fused" if "fused" in parts else parts[0]
-    launches = {"fused": 1, "ring": 2 * (N - 1), "pack": R, "unpack": R, "rs": 1, "ag": 1,
-                "chunked": 2 * (N - 1), "failover": 2, "packed": R}[head]
+    fused_launches = nz.nz_allreduce_launches(N, n, w.ratios, w.dtype, "fused", K)
+    launches = {"fused": fused_launches, "ring": 2 * (N - 1), "pack": R, "unpack": R, "rs": 1, "ag": 1,
+                "chunked": 2 * (N - 1), "failover": 2, "packed": R, "packed_out": R, "unpack_out": R}[head]
+    fused_kernel = "nz_fused_stage" if fused_launches > 1 else "nz_fused_reduce_bcast"
     achieved = part_stats[head]["hbm_GBps"]
     roofline = {
-        "kernel": {"fused": "nz_fused_reduce_bcast", "ring": "nz_ring_step",
+        "kernel": {"fused": fused_kernel, "ring": "nz_ring_step",
                    "pack": "nz_segment_copy", "unpack": "nz_segment_copy",
                    "rs": "nz_fused_reduce_bcast", "ag": "nz_gather_bcast",
-                   "chunked": "nz_ring_step", "failover": "nz_fused_reduce_bcast",
-                   "packed": "nz_fused_reduce_bcast"}[head],
+                   "chunked": "nz_ring_wave", "failover": "nz_fused_reduce_bcast",
+                   "packed": fused_kernel, "packed_out": fused_kernel, "unpack_out": "nz_segment_copy"}[head],
         "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "launches": launches,
         "algorithmic_bytes_per_launch": alg_bytes[head] // launches,
         "avg_launch_ms": round(part_stats[head]["ms"] / launches, 4),
         "traffic": recorded_traffic(f"{head}_{w.name}"),
@@ -394,22 +469,21 @@ def main() -> int:
         "roofline": roofline,
         "device": device_facts(torch),
     }
-    if packed_ref_outs is not None:
-        # The same fused call with its outputs in the inputs' region, for reference.
-        ev = []
-        for i in range(5):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            nz.nz_allreduce_sim(ins, n, w.ratios, w.dtype, "fused", packed_ref_outs)
-            b.record()
-            ev.append((a, b))
-        torch.cuda.synchronize()
-        ms = sum(a.elapsed_time(b) for a, b in ev[1:]) / (len(ev) - 1)
-        out["fused_with_outputs_in_one_region"] = {
-            "ms": round(ms, 4), "hbm_GBps": round(alg_bytes["fused"] / (ms * 1e-3) / 1e9, 1),
-            "frac_of_peak": round(alg_bytes["fused"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)}
+    if args.placement != "torch" and arena is not None and not args.no_plain and not args.graph:
+        # The same parts once more on plain allocations: what a caller gets who leaves
+        # placement to the allocator.
+        bufs.clear()
+        del ins, outs, send, arena
+        torch.cuda.empty_cache()
+        p_ins, p_outs, p_send, _, _ = make_buffers("torch")
+        bufs.update(ins=p_ins, outs=p_outs, send=p_send)
+        plain = time_parts(reps=5, warm=2)
+        out["plain_allocations"] = {"placement": "plain torch allocations", "parts": plain,
+                                    "roofline_frac": plain[head]["frac_of_peak"]}
+        del p_ins, p_outs, p_send
     if not args.no_cpu_baseline:
-        del ins, outs, send, packed_ref_outs, arena
+        bufs.clear()
+        ins = outs = send = arena = None
         torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_sample_elems, parts)
     print(json.dumps(out), flush=True)

@@ -690,6 +690,9 @@ double orc_efficiency_ratio(double t_setup_i, double bw_i, double S_i,
 #ifdef _OPENMP
 #include <omp.h>
 int orc_threads(void) { return omp_get_max_threads(); }
+/* Number of host threads the definitional sums use from now on (timing aid; no arithmetic). */
+void orc_set_threads(int n) { if (n > 0) omp_set_num_threads(n); }
 #else
 int orc_threads(void) { return 1; }
+void orc_set_threads(int n) { (void)n; }
 #endif

@@ -25,7 +25,7 @@ ELEM_BYTES = {F32: 4, BF16: 2, F16: 2, I32: 4}
 _NP_STORAGE = {F32: np.float32, BF16: np.uint16, F16: np.uint16, I32: np.int32}
 
 __all__ = [
-    "F32", "BF16", "F16", "I32", "ELEM_BYTES", "build", "threads",
+    "F32", "BF16", "F16", "I32", "ELEM_BYTES", "build", "threads", "set_threads",
     "rail_partition", "segment_map", "sum_float", "sum_i32", "round_to_storage",
     "ring_allreduce", "ring_allgather", "ring_allreduce_chunked", "failover_target", "pack", "unpack",
     "t_cold", "t_hot", "balance_iterate", "balance_optimum", "threshold", "net_efficiency", "efficiency_ratio",
@@ -86,6 +86,8 @@ def _L():
         lib.orc_f32_to_f16.argtypes = [ctypes.c_float]
         lib.orc_f32_to_f16.restype = ctypes.c_uint16
         lib.orc_threads.restype = ctypes.c_int
+        lib.orc_set_threads.argtypes = [ctypes.c_int]
+        lib.orc_set_threads.restype = None
         _lib = lib
     return _lib
 
@@ -98,6 +100,11 @@ def _check(rc: int, what: str) -> None:
 def threads() -> int:
     """Number of host threads the definitional sums use."""
     return int(_L().orc_threads())
+
+
+def set_threads(n: int) -> None:
+    """Host threads for the definitional sums from now on (used to time one thread and all)."""
+    _L().orc_set_threads(int(n))
 
 
 def storage_dtype(dtype: int):

@@ -10,7 +10,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libnezha_sim.so")
 SOURCES = [os.path.join(CSRC, "nz_host.hip"), os.path.join(CSRC, "nz_index.cpp"),
-           os.path.join(CSRC, "nz_balance.cpp")]
+           os.path.join(CSRC, "nz_balance.cpp"), os.path.join(CSRC, "nz_validate.cpp"),
+           os.path.join(CSRC, "nz_placement.cpp")]
 
 
 def hipcc() -> str:

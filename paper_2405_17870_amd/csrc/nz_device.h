@@ -89,15 +89,15 @@ __device__ __forceinline__ void decode_block(const NZ_KARG RailGeom &g, u32 bloc
 // boundary is; the first and last tile of a segment are simply shorter.
 template <int TILE_VECS>
 __device__ __forceinline__ SegTile segment_tile(const NZ_KARG RailGeom &g, u32 rail, u32 seg, u32 tile,
-                                                u32 elem_shift)
+                                                u32 elem_shift, u64 win_off, u64 win_len)
 {
     SegTile t;
     const u32 rem = g.rem[rail];
     u64 beg = g.off[rail] + seg * g.q[rail] + (seg < rem ? seg : rem);
     u64 len = g.q[rail] + (seg < rem ? 1u : 0u);
-    const u64 skip = len < g.win_off ? len : g.win_off;
+    const u64 skip = len < win_off ? len : win_off;
     beg += skip;
-    len = (len - skip) < g.win_len ? (len - skip) : g.win_len;
+    len = (len - skip) < win_len ? (len - skip) : win_len;
     t.b0 = beg << elem_shift;
     t.b1 = (beg + len) << elem_shift;
     const u64 v0 = t.b0 >> 4;
@@ -108,6 +108,14 @@ __device__ __forceinline__ SegTile segment_tile(const NZ_KARG RailGeom &g, u32 r
     t.vec_hi = end < v1 ? end : v1;
     if (len == 0) t.vec_hi = t.vec_lo;
     return t;
+}
+
+// The same for the window the launch as a whole works on.
+template <int TILE_VECS>
+__device__ __forceinline__ SegTile segment_tile(const NZ_KARG RailGeom &g, u32 rail, u32 seg, u32 tile,
+                                                u32 elem_shift)
+{
+    return segment_tile<TILE_VECS>(g, rail, seg, tile, elem_shift, g.win_off, g.win_len);
 }
 
 // ---------------------------------------------------------------------------
@@ -312,6 +320,12 @@ struct ElemPacket {
 // Fused N-way reduce + broadcast
 // ---------------------------------------------------------------------------
 
+// A table of node buffer addresses inside a kernel-argument block.
+typedef const void *NodePtr;
+typedef const NZ_KARG NodePtr *NodeTable;
+typedef void *OutPtr;
+typedef const NZ_KARG OutPtr *OutTable;
+
 struct FusedArgs {
     RailGeom g;
     u32 n_out;       // distinct output buffers (broadcast form)
@@ -332,12 +346,12 @@ struct FusedArgs {
 // are independent and in flight together.
 // Sum of a full block of eight nodes starting at node m0: a balanced tree.
 template <class T, class P>
-__device__ __forceinline__ void block_sum8(const NZ_KARG FusedArgs &a, u32 m0, u64 byte_off,
+__device__ __forceinline__ void block_sum8(NodeTable in, u32 m0, u64 byte_off,
                                            typename T::acc_t (&s)[P::kLanes])
 {
     typename P::raw_t r[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) r[i] = P::load(a.in[m0 + i], byte_off);
+    for (int i = 0; i < 8; ++i) r[i] = P::load(in[m0 + i], byte_off);
 #pragma unroll
     for (int l = 0; l < P::kLanes; ++l)
         s[l] = ((P::lane(r[0], l) + P::lane(r[1], l)) + (P::lane(r[2], l) + P::lane(r[3], l))) +
@@ -347,13 +361,13 @@ __device__ __forceinline__ void block_sum8(const NZ_KARG FusedArgs &a, u32 m0, u
 // Sum of the last, partial block (1 <= nb <= 7 nodes): the same tree with the
 // missing leaves left out.
 template <class T, class P>
-__device__ __forceinline__ void block_sum_tail(const NZ_KARG FusedArgs &a, u32 m0, u32 nb,
-                                               u64 byte_off, typename T::acc_t (&s)[P::kLanes])
+__device__ __forceinline__ void block_sum_tail(NodeTable in, u32 m0, u32 nb, u64 byte_off,
+                                               typename T::acc_t (&s)[P::kLanes])
 {
     typedef typename T::acc_t acc_t;
     typename P::raw_t r[7];
 #pragma unroll
-    for (int i = 0; i < 7; ++i) r[i] = P::load(a.in[(u32)i < nb ? m0 + i : m0], byte_off);
+    for (int i = 0; i < 7; ++i) r[i] = P::load(in[(u32)i < nb ? m0 + i : m0], byte_off);
 #pragma unroll
     for (int l = 0; l < P::kLanes; ++l) {
         const acc_t p0 = nb > 1 ? P::lane(r[0], l) + P::lane(r[1], l) : P::lane(r[0], l);
@@ -366,13 +380,69 @@ __device__ __forceinline__ void block_sum_tail(const NZ_KARG FusedArgs &a, u32 m
     }
 }
 
+// How many nodes a kernel instantiation is built for.  The order of additions
+// is the same in all three; what differs is how many partial sums have to be
+// kept, i.e. registers, i.e. waves per SIMD (a message small enough to be
+// bound by latency, and the copy part of the staged kernel, want many).
+enum NodeClass {
+    kUpTo8 = 0,   // a single block: no running sums
+    kUpTo32 = 1,  // at most four blocks: each running sum is one block sum, so the
+                  // final tree (s0 + s1) + (s2 + s3) is built as the blocks arrive
+    kAnyN = 2     // the general form
+};
+
+// One block's sum, full or partial: block number blk of n_full full blocks.
 template <class T, class P>
-__device__ __forceinline__ void reduce_bcast_at(const NZ_KARG FusedArgs &a, u64 byte_off, u32 out_begin,
-                                                u32 out_end)
+__device__ __forceinline__ void block_sum(NodeTable in, u32 blk, u32 n_full, u32 n_tail, u64 byte_off,
+                                          typename T::acc_t (&s)[P::kLanes])
+{
+    if (blk < n_full)
+        block_sum8<T, P>(in, blk * 8, byte_off, s);
+    else
+        block_sum_tail<T, P>(in, blk * 8, n_tail, byte_off, s);
+}
+
+// The sum at one packet position, narrowed to the storage type.
+template <class T, class P, int CLASS>
+__device__ __forceinline__ typename P::raw_t reduce_at(NodeTable in, u32 N, u64 byte_off)
 {
     typedef typename T::acc_t acc_t;
     constexpr int L = P::kLanes;
-    const u32 N = a.g.n_nodes;
+    acc_t res[L];
+    if (CLASS == kUpTo8) {
+        if (N == 8)
+            block_sum8<T, P>(in, 0, byte_off, res);
+        else
+            block_sum_tail<T, P>(in, 0, N, byte_off, res);
+        return P::narrow(res);
+    }
+    if (CLASS == kUpTo32) {
+        const u32 n_full = N >> 3, n_tail = N & 7u, n_blocks = n_full + (n_tail ? 1u : 0u);
+        block_sum<T, P>(in, 0, n_full, n_tail, byte_off, res);
+        if (n_blocks > 1) {
+            acc_t s[L];
+            block_sum<T, P>(in, 1, n_full, n_tail, byte_off, s);
+#pragma unroll
+            for (int l = 0; l < L; ++l) res[l] = res[l] + s[l];
+        }
+        if (n_blocks > 2) {
+#pragma unroll
+            for (int l = 0; l < L; ++l) asm volatile("" : "+v"(res[l]) : : "memory");
+            acc_t u[L];
+            block_sum<T, P>(in, 2, n_full, n_tail, byte_off, u);
+            if (n_blocks > 3) {
+#pragma unroll
+                for (int l = 0; l < L; ++l) asm volatile("" : "+v"(u[l]) : : "memory");
+                acc_t s[L];
+                block_sum<T, P>(in, 3, n_full, n_tail, byte_off, s);
+#pragma unroll
+                for (int l = 0; l < L; ++l) u[l] = u[l] + s[l];
+            }
+#pragma unroll
+            for (int l = 0; l < L; ++l) res[l] = res[l] + u[l];
+        }
+        return P::narrow(res);
+    }
     const u32 n_full = N >> 3, n_tail = N & 7u;
     acc_t run[4][L];
     for (u32 b = 0; b < n_full; b += 4) {
@@ -380,15 +450,22 @@ __device__ __forceinline__ void reduce_bcast_at(const NZ_KARG FusedArgs &a, u64 
         for (int c = 0; c < 4; ++c) {
             if (b + c >= n_full) break;
             acc_t s[L];
-            block_sum8<T, P>(a, (b + c) * 8, byte_off, s);
+            block_sum8<T, P>(in, (b + c) * 8, byte_off, s);
 #pragma unroll
             for (int l = 0; l < L; ++l) run[c][l] = (b == 0) ? s[l] : run[c][l] + s[l];
+            // One block's eight loads in flight at a time: the running sum is
+            // pinned here and no memory access may cross, otherwise the loads of
+            // all four blocks are hoisted to the top, which triples the registers
+            // and costs the waves per SIMD that the copy part of the staged
+            // kernel needs.
+#pragma unroll
+            for (int l = 0; l < L; ++l) asm volatile("" : "+v"(run[c][l]) : : "memory");
         }
     }
     if (n_tail) {
         // The partial block is block number n_full: it goes to running sum n_full mod 4.
         acc_t s[L];
-        block_sum_tail<T, P>(a, n_full * 8, n_tail, byte_off, s);
+        block_sum_tail<T, P>(in, n_full * 8, n_tail, byte_off, s);
         const u32 slot = n_full & 3u;
         const bool first = n_full < 4;
 #pragma unroll
@@ -398,7 +475,6 @@ __device__ __forceinline__ void reduce_bcast_at(const NZ_KARG FusedArgs &a, u64 
                 for (int l = 0; l < L; ++l) run[c][l] = first ? s[l] : run[c][l] + s[l];
             }
     }
-    acc_t res[L];
 #pragma unroll
     for (int l = 0; l < L; ++l) {
         acc_t t = run[0][l];
@@ -410,8 +486,23 @@ __device__ __forceinline__ void reduce_bcast_at(const NZ_KARG FusedArgs &a, u64 
         }
         res[l] = t;
     }
-    const typename P::raw_t packed = P::narrow(res);
-    for (u32 o = out_begin; o < out_end; ++o) P::store(a.out[o], byte_off, packed);
+    return P::narrow(res);
+}
+
+// Reduce one packet position and store it to out[out_begin .. out_end).  The
+// stores start at a buffer that depends on the workgroup, so that workgroups
+// running at the same time write to different buffers.
+template <class T, class P, int CLASS>
+__device__ __forceinline__ void reduce_bcast_at(const NZ_KARG FusedArgs &a, u64 byte_off, u32 out_begin,
+                                                u32 out_end)
+{
+    const typename P::raw_t packed = reduce_at<T, P, CLASS>(a.in, a.g.n_nodes, byte_off);
+    const u32 K = out_end - out_begin;
+    u32 o = out_begin + blockIdx.x % K;
+    for (u32 i = 0; i < K; ++i) {
+        P::store(a.out[o], byte_off, packed);
+        if (++o == out_end) o = out_begin;
+    }
 }
 
 // The grid has two kinds of workgroups.  The first g.tile0[n_rails] of them
@@ -419,7 +510,7 @@ __device__ __forceinline__ void reduce_bcast_at(const NZ_KARG FusedArgs &a, u64 
 // vectors that lie wholly inside it.  They are followed by one workgroup per
 // (rail, segment) for the elements that share a 16-byte vector with a
 // neighbouring segment or with the end of the buffer: one thread per element.
-template <class T>
+template <class T, int CLASS>
 __global__ __launch_bounds__(kThreads) void nz_fused_reduce_bcast(const FusedArgs)
 {
     const NZ_KARG FusedArgs &a = kernel_args<FusedArgs>();
@@ -434,7 +525,7 @@ __global__ __launch_bounds__(kThreads) void nz_fused_reduce_bcast(const FusedArg
         const u64 vec = t.tile_base + threadIdx.x;
         const u32 owner = (seg == 0 ? a.g.n_nodes : seg) - 1;
         const u32 o0 = a.owner_only ? owner : 0, o1 = a.owner_only ? owner + 1 : a.n_out;
-        if (vec >= lo && vec < hi) reduce_bcast_at<T, VecPacket<T>>(a, vec << 4, o0, o1);
+        if (vec >= lo && vec < hi) reduce_bcast_at<T, VecPacket<T>, CLASS>(a, vec << 4, o0, o1);
         return;
     }
     const u32 e = blockIdx.x - n_tiles;
@@ -450,8 +541,85 @@ __global__ __launch_bounds__(kThreads) void nz_fused_reduce_bcast(const FusedArg
     const u64 eoff = (u64)lane << T::kShift;
     const u32 owner = (seg == 0 ? a.g.n_nodes : seg) - 1;
     const u32 o0 = a.owner_only ? owner : 0, o1 = a.owner_only ? owner + 1 : a.n_out;
-    if (part == 0 && t.b0 + eoff < head_end) reduce_bcast_at<T, ElemPacket<T>>(a, t.b0 + eoff, o0, o1);
-    if (part == 1 && tail_beg + eoff < t.b1) reduce_bcast_at<T, ElemPacket<T>>(a, tail_beg + eoff, o0, o1);
+    if (part == 0 && t.b0 + eoff < head_end) reduce_bcast_at<T, ElemPacket<T>, CLASS>(a, t.b0 + eoff, o0, o1);
+    if (part == 1 && tail_beg + eoff < t.b1)
+        reduce_bcast_at<T, ElemPacket<T>, CLASS>(a, tail_beg + eoff, o0, o1);
+}
+
+// ---------------------------------------------------------------------------
+// Fused reduce + broadcast of a large message, staged through one output
+// ---------------------------------------------------------------------------
+//
+// Writing K output streams at once from every workgroup is what the memory
+// system likes least: with all buffers in one region of HBM the single-pass
+// kernel above reaches 60-67 % of peak, while one write stream at a time
+// reaches 85 %.  For large messages the work is therefore cut into pieces of
+// a rail (kStagePieceBytes each) and issued as a short pipeline of launches;
+// launch c holds two kinds of workgroups:
+//   - "reduce": piece c is read once from all N nodes, summed as above and
+//     stored (streaming) to the first distinct output buffer only;
+//   - "spread": piece c - 1, finished by the previous launch, is copied from
+//     that buffer to every other output buffer, one buffer after the other
+//     (buffer index slowest in the grid).  The first pass over the piece
+//     brings it into the L2 caches, the other K - 2 passes read it there.
+// A piece is sized so that the share of it that one XCD's L2 sees (workgroup
+// b runs on XCD b mod 8, and the tile a workgroup copies depends on b mod 8
+// alone because all counts are padded to multiples of 8) stays below the L2
+// capacity of 4 MB.  Every sum is still read once per node, computed once in
+// registers and written once per output; the extra traffic is one cached
+// re-read of the result.
+constexpr u64 kStagePieceBytes = 24ull << 20;
+#ifndef NZ_STAGE_COPY_ITERS
+#define NZ_STAGE_COPY_ITERS 1
+#endif
+constexpr int kStageCopyIters = NZ_STAGE_COPY_ITERS;  // vectors per thread of the spread part
+
+struct StageArgs {
+    u64 a_lo, a_hi;   // bytes [a_lo, a_hi) of every buffer reduced by this launch; a_lo is a multiple of 16
+    u64 b_lo, b_hi;   // bytes copied from out[0] to out[1 .. n_out) by this launch; b_lo likewise
+    u32 n_a_blocks;   // workgroups of the reduce part (a multiple of 8)
+    u32 b_tiles;      // workgroups per output buffer of the spread part (a multiple of 8),
+                      // kStageCopyIters * 256 vectors each
+    u32 n_nodes, n_out;
+    const void *in[NZ_MAX_NODES];
+    void *out[NZ_MAX_NODES];
+};
+
+template <class T, int CLASS>
+__global__ __launch_bounds__(kThreads) void nz_fused_stage(const StageArgs)
+{
+    const NZ_KARG StageArgs &a = kernel_args<StageArgs>();
+    if (blockIdx.x < a.n_a_blocks) {
+        const u64 b0 = a.a_lo + (((u64)blockIdx.x * kThreads + threadIdx.x) << 4);
+        if (b0 + 16 <= a.a_hi) {
+            VecPacket<T>::store(a.out[0], b0, reduce_at<T, VecPacket<T>, CLASS>(a.in, a.n_nodes, b0));
+        } else if (b0 < a.a_hi) {
+            // the end of the message inside a vector: element by element
+            for (u64 b = b0; b < a.a_hi; b += sizeof(typename T::elem_t))
+                ElemPacket<T>::store(a.out[0], b, reduce_at<T, ElemPacket<T>, CLASS>(a.in, a.n_nodes, b));
+        }
+        return;
+    }
+    const u32 bb = blockIdx.x - a.n_a_blocks;
+    const u32 pass = bb / a.b_tiles, tile = bb - pass * a.b_tiles;
+    const void *src = a.out[0];
+    void *dst = a.out[1 + pass];
+    u64 b0[kStageCopyIters];
+    vec16 v[kStageCopyIters];
+#pragma unroll
+    for (int it = 0; it < kStageCopyIters; ++it) {
+        b0[it] = a.b_lo + ((((u64)tile * kStageCopyIters + it) * kThreads + threadIdx.x) << 4);
+        if (b0[it] + 16 <= a.b_hi) v[it] = VecPacket<T>::load_again(src, b0[it]);
+    }
+#pragma unroll
+    for (int it = 0; it < kStageCopyIters; ++it) {
+        if (b0[it] + 16 <= a.b_hi) {
+            VecPacket<T>::store(dst, b0[it], v[it]);
+        } else if (b0[it] < a.b_hi) {
+            for (u64 b = b0[it]; b < a.b_hi; b += sizeof(typename T::elem_t))
+                ElemPacket<T>::store(dst, b, ElemPacket<T>::load(src, b));
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -499,20 +667,21 @@ __device__ __forceinline__ void ring_at(const void *sent, const void *own, void 
         P::store(dst, byte_off, result);
 }
 
+// One workgroup's share of ring step `step`: tile `tile` of the piece
+// [win_off, win_off + g.win_len) of the segment node r of rail `rail` sends in
+// that step.
 template <class T, int ITERS, bool GATHER, bool REUSE>
-__global__ __launch_bounds__(kThreads) void nz_ring_step(const RingArgs)
+__device__ __forceinline__ void ring_tile(const NZ_KARG RingArgs &a, u32 rail, u32 r, u32 tile, u32 step,
+                                          u64 win_off)
 {
-    const NZ_KARG RingArgs &a = kernel_args<RingArgs>();
     constexpr int TILE = ITERS * kThreads;
-    u32 rail, r, tile;
-    decode_block(a.g, blockIdx.x, rail, r, tile);
     const u32 N = a.g.n_nodes;
     const u32 d = (r + 1 == N) ? 0 : r + 1;
-    const u32 seg = GATHER ? (r + 1 + N - a.step) % N : (r + N - a.step) % N;
-    const SegTile t = segment_tile<TILE>(a.g, rail, seg, tile, T::kShift);
+    const u32 seg = GATHER ? (r + 1 + N - step) % N : (r + N - step) % N;
+    const SegTile t = segment_tile<TILE>(a.g, rail, seg, tile, T::kShift, win_off, a.g.win_len);
     if (t.vec_lo >= t.vec_hi) return;
 
-    const void *sent = (GATHER || a.step > 0) ? a.out[r] : a.in[r];
+    const void *sent = (GATHER || step > 0) ? a.out[r] : a.in[r];
     const void *own = a.in[d];
     void *dst = a.out[d];
 
@@ -534,44 +703,140 @@ __global__ __launch_bounds__(kThreads) void nz_ring_step(const RingArgs)
         ring_at<T, ElemPacket<T>, GATHER, REUSE>(sent, own, dst, tail_beg + eoff);
 }
 
-// Direct allgather: every segment is read once from the node that owns it
-// after a reduce-scatter, node (j - 1) mod N for segment j, and stored to all
-// other nodes' buffers.  Same tiling as a ring step; a pure copy, so T only
-// fixes the element size of the edge path.
-template <class P>
-__device__ __forceinline__ void gather_at(const NZ_KARG RingArgs &a, u32 owner, u64 byte_off)
+// One ring step over all rails and nodes (the piece the launch works on is in
+// the geometry).
+template <class T, int ITERS, bool GATHER, bool REUSE>
+__global__ __launch_bounds__(kThreads) void nz_ring_step(const RingArgs)
 {
-    const typename P::raw_t v = P::load(a.out[owner], byte_off);
-    for (u32 m = 0; m < a.g.n_nodes; ++m)
-        if (m != owner) P::store(a.out[m], byte_off, v);
+    const NZ_KARG RingArgs &a = kernel_args<RingArgs>();
+    u32 rail, r, tile;
+    decode_block(a.g, blockIdx.x, rail, r, tile);
+    ring_tile<T, ITERS, GATHER, REUSE>(a, rail, r, tile, a.step, a.g.win_off);
+}
+
+// Ring_Chunked as a pipeline: the 2 (N - 1) steps of the ring are numbered
+// u = 0 .. 2N - 3 (reduce-scatter steps first), a segment transfer is cut into
+// pieces, and launch number w handles, for every piece c it has, step
+// u = w - c of that piece: piece 0 is one step ahead of piece 1, which is one
+// step ahead of piece 2, and so on -- what a pipeline of pieces looks like at
+// one moment.  Pieces cover disjoint elements, so the piece-steps of one
+// launch are independent, and a piece's step u runs one launch after its step
+// u - 1.  A rail with shorter segments has fewer pieces; the launch holds
+// workgroups only for the pieces a rail really has: rail k contributes pieces
+// piece_lo[k] .. piece_lo[k] + n - 1, n following from block0, with
+// N * g.tps[k] workgroups per piece (node, then tile).
+struct RingWaveArgs {
+    RingArgs ring;                 // ring.step and ring.g.tile0 are not used
+    u32 wave;                      // w
+    u32 piece_lo[NZ_MAX_RAILS];    // first piece of each rail in this launch
+    u32 block0[NZ_MAX_RAILS + 1];  // first workgroup of each rail in this launch
+};
+
+template <class T, int ITERS, bool REUSE>
+__global__ __launch_bounds__(kThreads) void nz_ring_wave(const RingWaveArgs)
+{
+    const NZ_KARG RingWaveArgs &w = kernel_args<RingWaveArgs>();
+    const NZ_KARG RingArgs &a = w.ring;
+    u32 rail = 0;
+    while (rail + 1 < a.g.n_rails && blockIdx.x >= w.block0[rail + 1]) ++rail;
+    const u32 tps = a.g.tps[rail], N = a.g.n_nodes;
+    u32 rest = blockIdx.x - w.block0[rail];
+    const u32 tile = rest % tps;
+    rest /= tps;
+    const u32 r = rest % N, piece = w.piece_lo[rail] + rest / N;
+    const u32 u = w.wave - piece, half = N - 1;
+    const u64 win_off = (u64)piece * a.g.win_len;
+    if (u < half)
+        ring_tile<T, ITERS, false, REUSE>(a, rail, r, tile, u, win_off);
+    else
+        ring_tile<T, ITERS, true, REUSE>(a, rail, r, tile, u - half, win_off);
+}
+
+// Direct allgather: every segment is read from the node that owns it after a
+// reduce-scatter, node (j - 1) mod N for segment j, and stored to the other
+// N - 1 nodes' buffers.
+//
+// Long segments go one destination buffer after the other, because one write
+// stream at a time is what the memory system handles best: a segment is
+// worked on in pieces small enough for the L2 caches (g.win_len elements;
+// g.tps workgroups per piece, a multiple of 8, so that a tile is always
+// copied by the same XCD); the first destination's pass brings the piece into
+// L2, the other N - 2 passes read it there.  Short segments (a piece is gone
+// before a second workgroup wave could follow it) are read once and stored to
+// all destinations by the same workgroup.  grp[k] is the number of
+// destinations a workgroup of rail k serves: 1 or N - 1.  Workgroup order
+// within a rail: segment, piece, destination group, tile.  A pure copy, so T
+// only fixes the element size of the edge path.
+struct GatherArgs {
+    RailGeom g;
+    u32 pps[NZ_MAX_RAILS];  // pieces per segment of each rail
+    u32 grp[NZ_MAX_RAILS];  // destinations per workgroup of each rail
+    void *buf[NZ_MAX_NODES];
+};
+
+template <class P>
+__device__ __forceinline__ typename P::raw_t gather_load(const NZ_KARG GatherArgs &a, u32 owner, bool once,
+                                                         u64 byte_off)
+{
+    return once ? P::load(a.buf[owner], byte_off) : P::load_again(a.buf[owner], byte_off);
+}
+
+template <class P>
+__device__ __forceinline__ void gather_at(const NZ_KARG GatherArgs &a, u32 owner, u32 d0, u32 d1, bool once,
+                                          u64 byte_off)
+{
+    const typename P::raw_t v = gather_load<P>(a, owner, once, byte_off);
+    for (u32 d = d0; d < d1; ++d) P::store(a.buf[d < owner ? d : d + 1], byte_off, v);  // the nodes other than the owner
 }
 
 template <class T, int ITERS>
-__global__ __launch_bounds__(kThreads) void nz_gather_bcast(const RingArgs)
+__global__ __launch_bounds__(kThreads) void nz_gather_bcast(const GatherArgs)
 {
-    const NZ_KARG RingArgs &a = kernel_args<RingArgs>();
+    const NZ_KARG GatherArgs &a = kernel_args<GatherArgs>();
     constexpr int TILE = ITERS * kThreads;
-    u32 rail, seg, tile;
-    decode_block(a.g, blockIdx.x, rail, seg, tile);
-    const SegTile t = segment_tile<TILE>(a.g, rail, seg, tile, T::kShift);
+    const u32 N = a.g.n_nodes;
+    u32 rail = 0;
+    while (rail + 1 < a.g.n_rails && blockIdx.x >= a.g.tile0[rail + 1]) ++rail;
+    const u32 grp = a.grp[rail], n_groups = (N - 1 + grp - 1) / grp;
+    u32 rest = blockIdx.x - a.g.tile0[rail];
+    const u32 tile = rest % a.g.tps[rail];
+    rest /= a.g.tps[rail];
+    const u32 group = rest % n_groups;
+    rest /= n_groups;
+    const u32 piece = rest % a.pps[rail], seg = rest / a.pps[rail];
+    const SegTile t =
+        segment_tile<TILE>(a.g, rail, seg, tile, T::kShift, (u64)piece * a.g.win_len, a.g.win_len);
     if (t.vec_lo >= t.vec_hi) return;
-    const u32 owner = (seg == 0 ? a.g.n_nodes : seg) - 1;
+    const u32 owner = (seg == 0 ? N : seg) - 1;
+    const u32 d0 = group * grp, d1 = d0 + grp < N - 1 ? d0 + grp : N - 1;
+    const bool once = n_groups == 1;
 
     const u64 full_lo = (t.b0 + 15) >> 4, full_hi = t.b1 >> 4;
     const u64 lo = t.vec_lo > full_lo ? t.vec_lo : full_lo;
     const u64 hi = t.vec_hi < full_hi ? t.vec_hi : full_hi;
+    // All of the thread's loads first, then the stores, destination by destination.
+    vec16 v[ITERS];
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         const u64 vec = t.tile_base + (u64)it * kThreads + threadIdx.x;
-        if (vec >= lo && vec < hi) gather_at<VecPacket<T>>(a, owner, vec << 4);
+        if (vec >= lo && vec < hi) v[it] = gather_load<VecPacket<T>>(a, owner, once, vec << 4);
+    }
+    for (u32 d = d0; d < d1; ++d) {
+        void *dst = a.buf[d < owner ? d : d + 1];  // the nodes other than the owner
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const u64 vec = t.tile_base + (u64)it * kThreads + threadIdx.x;
+            if (vec >= lo && vec < hi) VecPacket<T>::store(dst, vec << 4, v[it]);
+        }
     }
     const u64 head_end = (full_lo << 4) < t.b1 ? (full_lo << 4) : t.b1;
     u64 tail_beg = full_hi << 4;
     if (tail_beg < head_end) tail_beg = head_end;
     const u64 eoff = (u64)threadIdx.x << T::kShift;
-    if (t.vec_lo == (t.b0 >> 4) && t.b0 + eoff < head_end) gather_at<ElemPacket<T>>(a, owner, t.b0 + eoff);
+    if (t.vec_lo == (t.b0 >> 4) && t.b0 + eoff < head_end)
+        gather_at<ElemPacket<T>>(a, owner, d0, d1, once, t.b0 + eoff);
     if (t.vec_hi == ((t.b1 + 15) >> 4) && tail_beg + eoff < t.b1)
-        gather_at<ElemPacket<T>>(a, owner, tail_beg + eoff);
+        gather_at<ElemPacket<T>>(a, owner, d0, d1, once, tail_beg + eoff);
 }
 
 // ---------------------------------------------------------------------------

@@ -12,7 +12,6 @@
 #include <cstdlib>
 #include <cstring>
 #include <utility>
-#include <vector>
 
 #include "nz_device.h"
 
@@ -104,61 +103,100 @@ u64 build_geometry(RailGeom &g, const u64 *rail_off, u32 n_rails, u32 n_nodes, u
     return total == 0 ? kNothingToDo : total;
 }
 
-struct PtrRef {
-    uintptr_t p;
-    bool written;
-};
-
-// Buffers of `bytes` bytes each: a written buffer may not partially overlap
-// any other buffer.
-bool partial_overlap(std::vector<PtrRef> &v, u64 bytes)
-{
-    std::sort(v.begin(), v.end(), [](const PtrRef &x, const PtrRef &y) { return x.p < y.p; });
-    // merge equal pointers
-    size_t w = 0;
-    for (size_t i = 0; i < v.size(); ++i) {
-        if (w > 0 && v[w - 1].p == v[i].p)
-            v[w - 1].written = v[w - 1].written || v[i].written;
-        else
-            v[w++] = v[i];
-    }
-    v.resize(w);
-    for (size_t i = 0; i + 1 < v.size(); ++i)
-        if (v[i + 1].p - v[i].p < bytes && (v[i].written || v[i + 1].written)) return true;
-    return false;
-}
-
-struct Range {
-    uintptr_t lo, hi;
-    bool written;
-};
-
-// True if a written range overlaps any other range (read ranges may overlap
-// each other freely).
-bool written_range_overlaps(std::vector<Range> &v)
-{
-    std::sort(v.begin(), v.end(), [](const Range &x, const Range &y) { return x.lo < y.lo; });
-    uintptr_t end_any = 0, end_written = 0;
-    for (const Range &r : v) {
-        if (r.lo == r.hi) continue;
-        if (r.written ? r.lo < end_any : r.lo < end_written) return true;
-        end_any = std::max(end_any, r.hi);
-        if (r.written) end_written = std::max(end_written, r.hi);
-    }
-    return false;
-}
-
 template <class T>
 nz_status launch_fused(const FusedArgs &a, u32 blocks, hipStream_t st)
 {
-    const hipError_t e = launch(nz_fused_reduce_bcast<T>, blocks, a, st);
+    const hipError_t e = a.g.n_nodes <= 8    ? launch(nz_fused_reduce_bcast<T, kUpTo8>, blocks, a, st)
+                         : a.g.n_nodes <= 32 ? launch(nz_fused_reduce_bcast<T, kUpTo32>, blocks, a, st)
+                                             : launch(nz_fused_reduce_bcast<T, kAnyN>, blocks, a, st);
     return e == hipSuccess ? NZ_OK : hip_failed(e, "fused reduce launch");
 }
 
+// Payload per node from which the fused allreduce with several output buffers
+// is issued as the staged pipeline (see nz_fused_stage); below it the single
+// launch is faster.
+#ifndef NZ_STAGE_MIN_BYTES
+#define NZ_STAGE_MIN_BYTES (8ull << 20)
+#endif
+constexpr u64 kStageMinBytes = NZ_STAGE_MIN_BYTES;
+// A message shorter than one full piece is still cut into this many pieces (of
+// at least kStageSmallestPiece bytes), so that its reduce and spread parts overlap.
+#ifndef NZ_STAGE_MIN_PIECES
+#define NZ_STAGE_MIN_PIECES 1
+#endif
+constexpr u64 kStageMinPieces = NZ_STAGE_MIN_PIECES;
+constexpr u64 kStageSmallestPiece = 2ull << 20;
+
+u64 round_up(u64 x, u64 m) { return (x + m - 1) / m * m; }
+
+template <class T>
+nz_status launch_stage(StageArgs &a, hipStream_t st)
+{
+    constexpr u64 kTileBytes = (u64)kThreads * 16;
+    const u64 n_a = round_up((a.a_hi - a.a_lo + kTileBytes - 1) / kTileBytes, 8);
+    const u64 b_tiles =
+        round_up((a.b_hi - a.b_lo + kStageCopyIters * kTileBytes - 1) / (kStageCopyIters * kTileBytes), 8);
+    const u64 blocks = n_a + b_tiles * (a.n_out - 1);
+    if (blocks == 0) return NZ_OK;
+    if (blocks > 0x7fffffffull) return NZ_ERR_UNSUPPORTED;
+    a.n_a_blocks = (u32)n_a;
+    a.b_tiles = (u32)b_tiles;
+    const hipError_t e = a.n_nodes <= 8    ? launch(nz_fused_stage<T, kUpTo8>, (u32)blocks, a, st)
+                         : a.n_nodes <= 32 ? launch(nz_fused_stage<T, kUpTo32>, (u32)blocks, a, st)
+                                           : launch(nz_fused_stage<T, kAnyN>, (u32)blocks, a, st);
+    return e == hipSuccess ? NZ_OK : hip_failed(e, "staged fused launch");
+}
+
+// The staged pipeline over the participating rails: neighbouring rails form
+// one span of bytes; a span is cut into equal pieces of at most
+// kStagePieceBytes; launch c reduces piece c and spreads piece c - 1.
+template <class T>
+nz_status launch_staged(StageArgs &a, const u64 *rail_off, u32 n_rails, u32 rail_mask, u32 elem_shift,
+                        hipStream_t st)
+{
+    // More pieces than any memory holds: refuse before anything is launched.
+    if ((rail_off[n_rails] << elem_shift) / kStagePieceBytes > (1u << 16)) return NZ_ERR_UNSUPPORTED;
+    u64 spread_lo = 0, spread_hi = 0;  // the piece the next launch spreads
+    u32 k = 0;
+    while (k < n_rails) {
+        if (!(rail_mask >> k & 1u) || rail_off[k + 1] == rail_off[k]) {
+            ++k;
+            continue;
+        }
+        u32 end = k + 1;
+        while (end < n_rails && (rail_mask >> end & 1u)) ++end;
+        const u64 lo = rail_off[k] << elem_shift, hi = rail_off[end] << elem_shift;
+        k = end;
+        if (hi == lo) continue;
+        u64 n_pieces = (hi - lo + kStagePieceBytes - 1) / kStagePieceBytes;
+        n_pieces = std::max<u64>(n_pieces, std::min<u64>(kStageMinPieces, (hi - lo) / kStageSmallestPiece));
+        if (n_pieces == 0) n_pieces = 1;
+        const u64 piece = round_up((hi - lo + n_pieces - 1) / n_pieces, (u64)kThreads * 16);
+        for (u64 p = lo; p < hi; p += piece) {
+            a.a_lo = p;
+            a.a_hi = std::min(hi, p + piece);
+            a.b_lo = spread_lo;
+            a.b_hi = spread_hi;
+            const nz_status ls = launch_stage<T>(a, st);
+            if (ls != NZ_OK) return ls;
+            spread_lo = a.a_lo;
+            spread_hi = a.a_hi;
+        }
+    }
+    a.a_lo = a.a_hi = 0;
+    a.b_lo = spread_lo;
+    a.b_hi = spread_hi;
+    return launch_stage<T>(a, st);
+}
+
 #ifndef NZ_RING_ITERS
-#define NZ_RING_ITERS 2
+#define NZ_RING_ITERS 1
 #endif
 constexpr int kRingIters = NZ_RING_ITERS;
+#ifndef NZ_GATHER_ITERS
+#define NZ_GATHER_ITERS 2
+#endif
+constexpr int kGatherIters = NZ_GATHER_ITERS;
 
 enum Collective { kAllreduce, kReduceScatter, kAllgather };
 
@@ -167,28 +205,58 @@ enum Collective { kAllreduce, kReduceScatter, kAllgather };
 constexpr u64 kRingReuseBytes = 128ull << 20;
 
 // The launches of a ring: N - 1 reduce-scatter steps, then N - 1 allgather
-// steps (one half only for the phase collectives).  n_pieces > 1 (Ring_Chunked):
-// every step is issued as n_pieces launches of a.g.win_len elements of every
-// segment each.  Pieces cover disjoint elements, so a piece's next step
-// depends on that piece's previous step only; the launches go piece by piece
-// (all steps of piece 0, then all steps of piece 1, ...), which is the order a
-// pipeline gives each piece and lets a piece's partial sums stay in cache
-// from the step that stores them to the step that sends them on.
+// steps (one half only for the phase collectives), each over whole segments.
 template <class T, bool REUSE>
-nz_status launch_ring_steps(RingArgs &a, u32 blocks, hipStream_t st, Collective what, u64 n_pieces)
+nz_status launch_ring_steps(RingArgs &a, u32 blocks, hipStream_t st, Collective what)
 {
     const u32 N = a.g.n_nodes;
-    for (u64 c = 0; c < n_pieces; ++c) {
-        a.g.win_off = c * (n_pieces > 1 ? a.g.win_len : 0);
-        for (u32 s = 0; s + 1 < N && what != kAllgather; ++s) {
-            a.step = s;
-            const hipError_t e = launch(nz_ring_step<T, kRingIters, false, REUSE>, blocks, a, st);
-            if (e != hipSuccess) return hip_failed(e, "ring reduce-scatter launch");
-        }
-        for (u32 s = 0; s + 1 < N && what != kReduceScatter; ++s) {
-            a.step = s;
-            const hipError_t e = launch(nz_ring_step<T, kRingIters, true, REUSE>, blocks, a, st);
-            if (e != hipSuccess) return hip_failed(e, "ring allgather launch");
+    for (u32 s = 0; s + 1 < N && what != kAllgather; ++s) {
+        a.step = s;
+        const hipError_t e = launch(nz_ring_step<T, kRingIters, false, REUSE>, blocks, a, st);
+        if (e != hipSuccess) return hip_failed(e, "ring reduce-scatter launch");
+    }
+    for (u32 s = 0; s + 1 < N && what != kReduceScatter; ++s) {
+        a.step = s;
+        const hipError_t e = launch(nz_ring_step<T, kRingIters, true, REUSE>, blocks, a, st);
+        if (e != hipSuccess) return hip_failed(e, "ring allgather launch");
+    }
+    return NZ_OK;
+}
+
+// Ring_Chunked: n_pieces pieces of a.g.win_len elements of every segment, each
+// going through the 2 (N - 1) steps; launch w carries step w - c of every
+// piece c that has such a step (see nz_ring_wave): n_pieces + 2 (N - 1) - 1
+// launches, each piece one step behind the piece before it.
+template <class T, bool REUSE>
+nz_status launch_ring_pipeline(const RingArgs &a, hipStream_t st, u64 n_pieces)
+{
+    RingWaveArgs w;
+    std::memset(&w, 0, sizeof w);
+    w.ring = a;
+    const u32 R = a.g.n_rails, N = a.g.n_nodes;
+    const u64 n_steps = 2ull * (N - 1);
+    u64 rail_pieces[NZ_MAX_RAILS];  // a rail with shorter segments has fewer pieces
+    for (u32 k = 0; k < R; ++k) {
+        const u64 longest = a.g.q[k] + (a.g.rem[k] ? 1 : 0);
+        rail_pieces[k] = (longest + a.g.win_len - 1) / a.g.win_len;
+    }
+    // Sizes first: nothing is launched if a launch would not fit a grid.
+    for (int pass = 0; pass < 2; ++pass) {
+        for (u64 wave = 0; wave + 1 < n_pieces + n_steps; ++wave) {
+            u64 blocks = 0;
+            for (u32 k = 0; k < R; ++k) {
+                const u64 lo = wave >= n_steps ? wave - n_steps + 1 : 0;  // first piece still on its way
+                const u64 started = std::min<u64>(wave + 1, rail_pieces[k]);  // pieces 0 .. started - 1 have begun
+                w.piece_lo[k] = (u32)lo;
+                w.block0[k] = (u32)blocks;
+                if (started > lo) blocks += (started - lo) * N * a.g.tps[k];
+                if (blocks > 0x7fffffffull) return NZ_ERR_UNSUPPORTED;
+            }
+            w.block0[R] = (u32)blocks;
+            if (pass == 0 || blocks == 0) continue;
+            w.wave = (u32)wave;
+            const hipError_t e = launch(nz_ring_wave<T, kRingIters, REUSE>, (u32)blocks, w, st);
+            if (e != hipSuccess) return hip_failed(e, "chunked ring launch");
         }
     }
     return NZ_OK;
@@ -208,15 +276,70 @@ u64 ring_launch_bytes(const RingArgs &a)
 template <class T>
 nz_status launch_ring(RingArgs &a, u32 blocks, hipStream_t st, Collective what, u64 n_pieces)
 {
-    return ring_launch_bytes(a) <= kRingReuseBytes ? launch_ring_steps<T, true>(a, blocks, st, what, n_pieces)
-                                                   : launch_ring_steps<T, false>(a, blocks, st, what, n_pieces);
+    if (n_pieces > 1) {
+        // What one launch stores: up to min(pieces, steps) piece-steps.
+        const u64 in_flight = std::min<u64>(n_pieces, 2ull * (a.g.n_nodes - 1));
+        return ring_launch_bytes(a) * in_flight <= kRingReuseBytes
+                   ? launch_ring_pipeline<T, true>(a, st, n_pieces)
+                   : launch_ring_pipeline<T, false>(a, st, n_pieces);
+    }
+    return ring_launch_bytes(a) <= kRingReuseBytes ? launch_ring_steps<T, true>(a, blocks, st, what)
+                                                   : launch_ring_steps<T, false>(a, blocks, st, what);
 }
 
 template <class T>
-nz_status launch_gather(const RingArgs &a, u32 blocks, hipStream_t st)
+nz_status launch_gather(const GatherArgs &a, u32 blocks, hipStream_t st)
 {
-    const hipError_t e = launch(nz_gather_bcast<T, kRingIters>, blocks, a, st);
+    const hipError_t e = launch(nz_gather_bcast<T, kGatherIters>, blocks, a, st);
     return e == hipSuccess ? NZ_OK : hip_failed(e, "direct allgather launch");
+}
+
+// Segment (piece) size from which the direct allgather serves one destination
+// buffer at a time.
+#ifndef NZ_GATHER_ONE_BY_ONE_BYTES
+#define NZ_GATHER_ONE_BY_ONE_BYTES (1ull << 20)
+#endif
+constexpr u64 kGatherOneByOneBytes = NZ_GATHER_ONE_BY_ONE_BYTES;
+
+// Geometry of the direct allgather: per rail N segments x pieces x (N - 1)
+// destinations x tiles.  Returns the number of workgroups (as build_geometry).
+u64 build_gather_geometry(GatherArgs &a, const u64 *rail_off, u32 n_rails, u32 n_nodes, u32 elem_shift,
+                          u32 tile_vecs, u32 rail_mask)
+{
+    std::memset(&a.g, 0, sizeof a.g);
+    RailGeom &g = a.g;
+    g.n_rails = n_rails;
+    g.n_nodes = n_nodes;
+    g.win_off = 0;
+    g.win_len = kStagePieceBytes >> elem_shift;
+    u64 total = 0;
+    for (u32 k = 0; k < n_rails; ++k) {
+        const u64 len = (rail_mask >> k & 1u) ? rail_off[k + 1] - rail_off[k] : 0;
+        g.off[k] = rail_off[k];
+        g.q[k] = len / n_nodes;
+        g.rem[k] = (u32)(len % n_nodes);
+        g.tile0[k] = (u32)total;
+        const u64 longest = g.q[k] + (g.rem[k] ? 1 : 0);
+        a.pps[k] = 1;
+        a.grp[k] = n_nodes - 1;
+        g.tps[k] = 0;
+        if (longest == 0) continue;
+        const u64 pieces = (longest + g.win_len - 1) / g.win_len;
+        // Pieces start anywhere: bound the tiles a piece can touch; a multiple of 8.
+        const u64 vecs = ((std::min<u64>(longest, g.win_len) << elem_shift) + 15) / 16 + 1;
+        const u64 tiles = round_up((vecs + tile_vecs - 1) / tile_vecs + 1, 8);
+        if (pieces > 0xffffffffull || tiles > 0xffffffffull) return 0;
+        a.pps[k] = (u32)pieces;
+        g.tps[k] = (u32)tiles;
+        // One destination at a time pays once a piece outlasts the workgroups in flight.
+        a.grp[k] = ((std::min<u64>(longest, g.win_len) << elem_shift) >= kGatherOneByOneBytes) ? 1 : n_nodes - 1;
+        const u64 groups = (n_nodes - 1 + a.grp[k] - 1) / a.grp[k];
+        total += (u64)n_nodes * pieces * groups * tiles;
+        if (total > 0x7fffffffull) return 0;
+    }
+    g.off[n_rails] = rail_off[n_rails];
+    g.tile0[n_rails] = (u32)total;
+    return total == 0 ? kNothingToDo : total;
 }
 
 nz_status segment_copy(const void *const *src, void *const *dst, u32 n_nodes, const u64 *seg_off,
@@ -232,7 +355,7 @@ nz_status segment_copy(const void *const *src, void *const *dst, u32 n_nodes, co
     const u64 *row = seg_off + (size_t)rail * (n_nodes + 1);
     for (u32 j = 0; j < n_nodes; ++j)
         if (row[j + 1] < row[j] || row[j + 1] > (UINT64_MAX >> 3)) return NZ_ERR_INVALID_ARG;
-    std::vector<bool> seen(n_nodes, false);
+    bool seen[NZ_MAX_NODES] = {};
     u64 total = 0;
     for (u32 i = 0; i < n_segs; ++i) {
         if (seg_ids[i] >= n_nodes) return NZ_ERR_INVALID_ARG;
@@ -250,20 +373,10 @@ nz_status segment_copy(const void *const *src, void *const *dst, u32 n_nodes, co
     }
     // A written range may not overlap any other range.  The packed side of
     // buffer m is [base, base + total), the node side is the rail's span.
-    {
-        std::vector<Range> ranges;
-        ranges.reserve(2 * n_nodes);
-        for (u32 m = 0; m < n_nodes && total > 0; ++m) {
-            const uintptr_t s0 = reinterpret_cast<uintptr_t>(src[m]), d0 = reinterpret_cast<uintptr_t>(dst[m]);
-            if (packing) {
-                ranges.push_back({s0 + node_span_lo, s0 + node_span_hi, false});
-                ranges.push_back({d0, d0 + total, true});
-            } else {
-                ranges.push_back({s0, s0 + total, false});
-                ranges.push_back({d0 + node_span_lo, d0 + node_span_hi, true});
-            }
-        }
-        if (written_range_overlaps(ranges)) return NZ_ERR_UNSUPPORTED;
+    if (total > 0) {
+        const nz_status os = packing ? nz::check_copy_buffers(src, dst, n_nodes, node_span_lo, node_span_hi, 0, total)
+                                     : nz::check_copy_buffers(src, dst, n_nodes, 0, total, node_span_lo, node_span_hi);
+        if (os != NZ_OK) return os;
     }
     if (packed_bytes) *packed_bytes = total;
     if (total == 0) return NZ_OK;
@@ -271,28 +384,29 @@ nz_status segment_copy(const void *const *src, void *const *dst, u32 n_nodes, co
     // Runs: consecutive list entries that are also consecutive in the node
     // buffer merge into one (a whole rail in order is a single run).
     struct Run { u64 node_off, pack_off, len; };
-    std::vector<Run> runs;
+    Run runs[NZ_MAX_NODES];
+    size_t n_runs = 0;
     u64 pos = 0;
     for (u32 i = 0; i < n_segs; ++i) {
         const u64 off = row[seg_ids[i]] * elem_bytes;
         const u64 len = (row[seg_ids[i] + 1] - row[seg_ids[i]]) * elem_bytes;
         if (len == 0) continue;
-        if (!runs.empty() && runs.back().node_off + runs.back().len == off)
-            runs.back().len += len;
+        if (n_runs > 0 && runs[n_runs - 1].node_off + runs[n_runs - 1].len == off)
+            runs[n_runs - 1].len += len;
         else
-            runs.push_back({off, pos, len});
+            runs[n_runs++] = {off, pos, len};
         pos += len;
     }
 
     constexpr u64 TILE = (u64)kCopyIters * kThreads;
     size_t next = 0;
-    while (next < runs.size()) {
+    while (next < n_runs) {
         CopyArgs a;
         std::memset(&a, 0, sizeof a);
         a.elem_bytes = elem_bytes;
         u64 blocks = 0;
         u32 r = 0;
-        for (; r < (u32)kCopyMaxRuns && next < runs.size(); ++r, ++next) {
+        for (; r < (u32)kCopyMaxRuns && next < n_runs; ++r, ++next) {
             const Run &run = runs[next];
             a.src_off[r] = packing ? run.node_off : run.pack_off;
             a.dst_off[r] = packing ? run.pack_off : run.node_off;
@@ -344,57 +458,27 @@ nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t
     }
     const u64 bytes = n_elems * eb;
     {
-        std::vector<PtrRef> refs;
-        refs.reserve(2 * n_nodes);
-        for (u32 i = 0; i < n_nodes; ++i) {
-            refs.push_back({reinterpret_cast<uintptr_t>(node_bufs[i]), false});
-            refs.push_back({reinterpret_cast<uintptr_t>(out_bufs[i]), true});
-        }
-        if (partial_overlap(refs, bytes)) return NZ_ERR_UNSUPPORTED;
-    }
-    if (mode == NZ_RING_STEPWISE || what != kAllreduce) {
-        // Outputs pairwise distinct; an output may alias only its own node's input.
-        std::vector<std::pair<uintptr_t, u32>> ins, outs;
-        for (u32 i = 0; i < n_nodes; ++i) {
-            ins.push_back({reinterpret_cast<uintptr_t>(node_bufs[i]), i});
-            outs.push_back({reinterpret_cast<uintptr_t>(out_bufs[i]), i});
-        }
-        std::sort(ins.begin(), ins.end());
-        std::sort(outs.begin(), outs.end());
-        for (u32 i = 0; i + 1 < n_nodes; ++i)
-            if (outs[i].first == outs[i + 1].first) return NZ_ERR_UNSUPPORTED;
-        for (u32 i = 0; i < n_nodes; ++i) {
-            auto it = std::lower_bound(ins.begin(), ins.end(), std::make_pair(outs[i].first, 0u));
-            for (; it != ins.end() && it->first == outs[i].first; ++it)
-                if (it->second != outs[i].second) return NZ_ERR_UNSUPPORTED;
-        }
+        const nz_status os = nz::check_collective_buffers(node_bufs, out_bufs, n_nodes, bytes,
+                                                          mode == NZ_RING_STEPWISE || what != kAllreduce);
+        if (os != NZ_OK) return os;
     }
     if (n_elems == 0) return NZ_OK;
 
     const u32 shift = (eb == 4) ? 2 : 1;
 
     if (mode == NZ_FUSED && what == kAllgather) {
-        RingArgs a;
-        const u64 blocks =
-            build_geometry(a.g, rail_off, n_rails, n_nodes, shift, (u32)kRingIters * kThreads, rail_mask);
+        if (n_nodes == 1) return NZ_OK;
+        GatherArgs a;
+        const u64 blocks = build_gather_geometry(a, rail_off, n_rails, n_nodes, shift,
+                                                 (u32)kGatherIters * kThreads, rail_mask);
         if (blocks == 0) return NZ_ERR_UNSUPPORTED;
         if (blocks == kNothingToDo) return NZ_OK;
-        a.elem_shift = shift;
-        a.step = 0;
-        for (u32 i = 0; i < n_nodes; ++i) {
-            a.in[i] = out_bufs[i];
-            a.out[i] = out_bufs[i];
-        }
-        if (n_nodes == 1) return NZ_OK;
+        for (u32 i = 0; i < n_nodes; ++i) a.buf[i] = out_bufs[i];
         return eb == 4 ? launch_gather<TI32>(a, (u32)blocks, st) : launch_gather<TBF16>(a, (u32)blocks, st);
     }
 
     if (mode == NZ_FUSED) {
         FusedArgs a;
-        u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, kThreads, rail_mask);
-        if (blocks == 0) return NZ_ERR_UNSUPPORTED;
-        if (blocks == kNothingToDo) return NZ_OK;
-        blocks += (u64)n_rails * n_nodes;  // the workgroups for segment edges
         a.owner_only = (what == kReduceScatter) ? 1u : 0u;
         a.n_out = 0;
         for (u32 i = 0; i < n_nodes; ++i) {
@@ -403,6 +487,29 @@ nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t
             for (u32 o = 0; o < a.n_out && !a.owner_only; ++o) dup = dup || (a.out[o] == out_bufs[i]);
             if (!dup) a.out[a.n_out++] = out_bufs[i];
         }
+        u64 active_bytes = 0;
+        for (u32 k = 0; k < n_rails; ++k)
+            if (rail_mask >> k & 1u) active_bytes += (rail_off[k + 1] - rail_off[k]) << shift;
+        if (what == kAllreduce && a.n_out >= 2 && active_bytes >= kStageMinBytes) {
+            // Large message, several outputs: the staged pipeline.
+            StageArgs sa;
+            std::memset(&sa, 0, sizeof sa);
+            sa.n_nodes = n_nodes;
+            sa.n_out = a.n_out;
+            for (u32 i = 0; i < n_nodes; ++i) sa.in[i] = a.in[i];
+            for (u32 i = 0; i < a.n_out; ++i) sa.out[i] = a.out[i];
+            switch (dtype) {
+            case NZ_F32: return launch_staged<TF32>(sa, rail_off, n_rails, rail_mask, shift, st);
+            case NZ_I32: return launch_staged<TI32>(sa, rail_off, n_rails, rail_mask, shift, st);
+            case NZ_BF16: return launch_staged<TBF16>(sa, rail_off, n_rails, rail_mask, shift, st);
+            case NZ_F16: return launch_staged<TF16>(sa, rail_off, n_rails, rail_mask, shift, st);
+            }
+            return NZ_ERR_INVALID_ARG;
+        }
+        u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, kThreads, rail_mask);
+        if (blocks == 0) return NZ_ERR_UNSUPPORTED;
+        if (blocks == kNothingToDo) return NZ_OK;
+        blocks += (u64)n_rails * n_nodes;  // the workgroups for segment edges
         switch (dtype) {
         case NZ_F32: return launch_fused<TF32>(a, (u32)blocks, st);
         case NZ_I32: return launch_fused<TI32>(a, (u32)blocks, st);
@@ -461,6 +568,32 @@ nz_status nz_allreduce_sim(const void *const *node_bufs, uint32_t n_nodes, uint6
     hipStream_t st = static_cast<hipStream_t>(stream);
     return finish(run_collective(kAllreduce, node_bufs, n_nodes, n_elems, ratios, n_rails, dtype, mode, out_bufs, st),
                   st);
+}
+
+nz_status nz_allreduce_launches(uint32_t n_nodes, uint64_t n_elems, const uint32_t *ratios, uint32_t n_rails,
+                                nz_dtype dtype, nz_mode mode, uint32_t n_distinct_outputs, uint64_t *launches)
+{
+    if (ratios == nullptr || launches == nullptr || n_nodes == 0 || n_rails == 0) return NZ_ERR_INVALID_ARG;
+    const u32 eb = nz_dtype_bytes(dtype);
+    if (eb == 0 || (mode != NZ_RING_STEPWISE && mode != NZ_FUSED)) return NZ_ERR_INVALID_ARG;
+    if (n_nodes > NZ_MAX_NODES || n_rails > NZ_MAX_RAILS) return NZ_ERR_UNSUPPORTED;
+    u64 rail_off[NZ_MAX_RAILS + 1];
+    const nz_status ps = nz::rail_partition(n_elems, eb, NZ_RAIL_ALIGN_BYTES, ratios, n_rails, rail_off);
+    if (ps != NZ_OK) return ps;
+    *launches = 0;
+    if (n_elems == 0) return NZ_OK;
+    if (mode == NZ_RING_STEPWISE) {
+        *launches = n_nodes > 1 ? 2ull * (n_nodes - 1) : (n_distinct_outputs > 0 ? 1 : 0);
+        return NZ_OK;
+    }
+    const u64 bytes = n_elems * eb;
+    if (n_distinct_outputs < 2 || bytes < kStageMinBytes) {
+        *launches = 1;
+        return NZ_OK;
+    }
+    // The staged pipeline: all rails take part, so the message is one span.
+    *launches = (bytes + kStagePieceBytes - 1) / kStagePieceBytes + 1;
+    return NZ_OK;
 }
 
 nz_status nz_reduce_scatter_sim(const void *const *node_bufs, uint32_t n_nodes, uint64_t n_elems,

@@ -34,7 +34,7 @@ EXPORTS = [
     "nz_rail_partition_ex", "nz_segment_map", "nz_allreduce_sim", "nz_reduce_scatter_sim",
     "nz_allgather_sim", "nz_allreduce_sim_chunked", "nz_failover_target",
     "nz_allreduce_sim_failover", "nz_pack", "nz_unpack", "nz_balance", "nz_balance_threshold",
-    "nz_balance_iterate",
+    "nz_balance_iterate", "nz_hbm_place", "nz_allreduce_launches",
     "nz_net_efficiency", "nz_efficiency_ratio",
 ]
 
@@ -90,6 +90,10 @@ def load() -> ctypes.CDLL:
     lib.nz_balance_threshold.restype = i32
     lib.nz_balance_iterate.argtypes = [vp, u32, ctypes.c_double, u32, vp, vp, vp, vp]
     lib.nz_balance_iterate.restype = i32
+    lib.nz_allreduce_launches.argtypes = [u32, u64, vp, u32, i32, i32, u32, vp]
+    lib.nz_allreduce_launches.restype = i32
+    lib.nz_hbm_place.argtypes = [u64, vp, u32, u64, i32, u32, vp]
+    lib.nz_hbm_place.restype = i32
     lib.nz_net_efficiency.argtypes = [vp, ctypes.c_double, vp]
     lib.nz_net_efficiency.restype = i32
     lib.nz_efficiency_ratio.argtypes = [vp, u32, ctypes.c_double, vp, vp]
@@ -114,10 +118,32 @@ def _u32_array(values: Sequence[int]):
     return (ctypes.c_uint32 * max(len(vals), 1))(*vals)
 
 
-def _ptr_array(tensors) -> ctypes.Array:
+_TORCH_DTYPE_NAME = {"f32": "torch.float32", "bf16": "torch.bfloat16", "f16": "torch.float16",
+                     "i32": "torch.int32"}
+
+
+def _ptr_array(tensors, min_elems: int = 0, dtype: Optional[str] = None,
+               elem_bytes: Optional[int] = None, what: str = "buffer") -> ctypes.Array:
+    """Host array of device addresses.  A torch tensor is checked before its address is taken --
+    on the device, contiguous, of the stated element type (or element size) and holding at
+    least ``min_elems`` elements -- because the kernels trust these facts; a raw integer
+    address is passed through as it is."""
     arr = (ctypes.c_void_p * max(len(tensors), 1))()
     for i, t in enumerate(tensors):
-        arr[i] = t.data_ptr() if hasattr(t, "data_ptr") else int(t)
+        if not hasattr(t, "data_ptr"):
+            arr[i] = int(t)
+            continue
+        if not t.is_cuda:
+            raise ValueError(f"{what} {i} is not a device tensor")
+        if not t.is_contiguous():
+            raise ValueError(f"{what} {i} is not contiguous")
+        if dtype is not None and str(t.dtype) != _TORCH_DTYPE_NAME[dtype]:
+            raise ValueError(f"{what} {i} has dtype {t.dtype}, the call says {dtype}")
+        if elem_bytes in (2, 4) and t.element_size() != elem_bytes:     # other sizes: the library refuses
+            raise ValueError(f"{what} {i} has {t.element_size()}-byte elements, the call says {elem_bytes}")
+        if t.numel() < min_elems:
+            raise ValueError(f"{what} {i} holds {t.numel()} elements, the call needs {min_elems}")
+        arr[i] = t.data_ptr()
     return arr
 
 
@@ -161,9 +187,20 @@ def nz_allreduce_sim(node_bufs: Sequence, n_elems: int, ratios: Sequence[int], d
     lib = load()
     if len(out_bufs) != len(node_bufs):
         raise ValueError("out_bufs must have one entry per node")
-    _check(lib.nz_allreduce_sim(_ptr_array(node_bufs), len(node_bufs), n_elems,
+    _check(lib.nz_allreduce_sim(_ptr_array(node_bufs, n_elems, dtype, what="node buffer"), len(node_bufs), n_elems,
                                 _u32_array(ratios), len(ratios), DTYPE_CODE[dtype],
-                                MODE_CODE[mode], _ptr_array(out_bufs), _stream_handle(stream)))
+                                MODE_CODE[mode], _ptr_array(out_bufs, n_elems, dtype, what="output buffer"),
+                                _stream_handle(stream)))
+
+
+def nz_allreduce_launches(n_nodes: int, n_elems: int, ratios: Sequence[int], dtype: str, mode: str,
+                          n_distinct_outputs: int) -> int:
+    """Kernel launches one nz_allreduce_sim call issues for these arguments.  Host only."""
+    lib = load()
+    out = ctypes.c_uint64(0)
+    _check(lib.nz_allreduce_launches(n_nodes, n_elems, _u32_array(ratios), len(ratios), DTYPE_CODE[dtype],
+                                     MODE_CODE[mode], n_distinct_outputs, ctypes.byref(out)))
+    return int(out.value)
 
 
 def nz_reduce_scatter_sim(node_bufs: Sequence, n_elems: int, ratios: Sequence[int], dtype: str,
@@ -173,9 +210,10 @@ def nz_reduce_scatter_sim(node_bufs: Sequence, n_elems: int, ratios: Sequence[in
     lib = load()
     if len(out_bufs) != len(node_bufs):
         raise ValueError("out_bufs must have one entry per node")
-    _check(lib.nz_reduce_scatter_sim(_ptr_array(node_bufs), len(node_bufs), n_elems,
+    _check(lib.nz_reduce_scatter_sim(_ptr_array(node_bufs, n_elems, dtype, what="node buffer"), len(node_bufs), n_elems,
                                      _u32_array(ratios), len(ratios), DTYPE_CODE[dtype],
-                                     MODE_CODE[mode], _ptr_array(out_bufs), _stream_handle(stream)))
+                                     MODE_CODE[mode], _ptr_array(out_bufs, n_elems, dtype, what="output buffer"),
+                                     _stream_handle(stream)))
 
 
 def nz_allgather_sim(bufs: Sequence, n_elems: int, ratios: Sequence[int], dtype: str, mode: str,
@@ -183,7 +221,7 @@ def nz_allgather_sim(bufs: Sequence, n_elems: int, ratios: Sequence[int], dtype:
     """The allgather half, in place (Sec. 2.1.1, Eq. 1): node r enters owning segment
     (r + 1) mod N of every rail; every buffer leaves holding every segment."""
     lib = load()
-    _check(lib.nz_allgather_sim(_ptr_array(bufs), len(bufs), n_elems, _u32_array(ratios),
+    _check(lib.nz_allgather_sim(_ptr_array(bufs, n_elems, dtype), len(bufs), n_elems, _u32_array(ratios),
                                 len(ratios), DTYPE_CODE[dtype], MODE_CODE[mode],
                                 _stream_handle(stream)))
 
@@ -195,9 +233,10 @@ def nz_allreduce_sim_chunked(node_bufs: Sequence, n_elems: int, ratios: Sequence
     lib = load()
     if len(out_bufs) != len(node_bufs):
         raise ValueError("out_bufs must have one entry per node")
-    _check(lib.nz_allreduce_sim_chunked(_ptr_array(node_bufs), len(node_bufs), n_elems,
+    _check(lib.nz_allreduce_sim_chunked(_ptr_array(node_bufs, n_elems, dtype, what="node buffer"), len(node_bufs), n_elems,
                                         _u32_array(ratios), len(ratios), DTYPE_CODE[dtype],
-                                        chunk_elems, _ptr_array(out_bufs), _stream_handle(stream)))
+                                        chunk_elems, _ptr_array(out_bufs, n_elems, dtype, what="output buffer"),
+                                        _stream_handle(stream)))
 
 
 def nz_failover_target(rail_off: Sequence[int], alive: Sequence[bool]) -> int:
@@ -220,9 +259,9 @@ def nz_allreduce_sim_failover(node_bufs: Sequence, n_elems: int, ratios: Sequenc
     if len(out_bufs) != len(node_bufs):
         raise ValueError("out_bufs must have one entry per node")
     t = ctypes.c_uint32(0)
-    _check(lib.nz_allreduce_sim_failover(_ptr_array(node_bufs), len(node_bufs), n_elems,
+    _check(lib.nz_allreduce_sim_failover(_ptr_array(node_bufs, n_elems, dtype, what="node buffer"), len(node_bufs), n_elems,
                                          _u32_array(ratios), len(ratios), DTYPE_CODE[dtype],
-                                         MODE_CODE[mode], _ptr_array(out_bufs), failed_rail,
+                                         MODE_CODE[mode], _ptr_array(out_bufs, n_elems, dtype, what="output buffer"), failed_rail,
                                          ctypes.byref(t), _stream_handle(stream)))
     return int(t.value)
 
@@ -237,8 +276,12 @@ def nz_pack(node_bufs: Sequence, seg_off: np.ndarray, rail: int, seg_ids: Sequen
     if len(node_bufs) != n_nodes or len(send_bufs) != n_nodes:
         raise ValueError("one node buffer and one send buffer per node")
     packed = ctypes.c_uint64(0)
-    _check(lib.nz_pack(_ptr_array(node_bufs), n_nodes, seg.ctypes.data, n_rails, rail,
-                       _u32_array(seg_ids), len(seg_ids), elem_bytes, _ptr_array(send_bufs),
+    sized = elem_bytes in (2, 4)             # any other element size is the library's to refuse
+    span = int(seg[rail, n_nodes]) if sized and 0 <= rail < n_rails else 0
+    cap_elems = -(-int(send_capacity_bytes) // elem_bytes) if sized else 0
+    _check(lib.nz_pack(_ptr_array(node_bufs, span, elem_bytes=elem_bytes, what="node buffer"), n_nodes,
+                       seg.ctypes.data, n_rails, rail, _u32_array(seg_ids), len(seg_ids), elem_bytes,
+                       _ptr_array(send_bufs, cap_elems, elem_bytes=elem_bytes, what="send buffer"),
                        send_capacity_bytes, ctypes.byref(packed), _stream_handle(stream)))
     return int(packed.value)
 
@@ -252,8 +295,12 @@ def nz_unpack(send_bufs: Sequence, seg_off: np.ndarray, rail: int, seg_ids: Sequ
     n_rails, n_nodes = seg.shape[0], seg.shape[1] - 1
     if len(node_bufs) != n_nodes or len(send_bufs) != n_nodes:
         raise ValueError("one node buffer and one send buffer per node")
-    _check(lib.nz_unpack(_ptr_array(send_bufs), n_nodes, seg.ctypes.data, n_rails, rail,
-                         _u32_array(seg_ids), len(seg_ids), elem_bytes, _ptr_array(node_bufs),
+    sized = elem_bytes in (2, 4) and 0 <= rail < n_rails
+    span = int(seg[rail, n_nodes]) if sized else 0
+    total = sum(int(seg[rail, j + 1] - seg[rail, j]) for j in seg_ids if 0 <= int(j) < n_nodes) if sized else 0
+    _check(lib.nz_unpack(_ptr_array(send_bufs, total, elem_bytes=elem_bytes, what="send buffer"), n_nodes,
+                         seg.ctypes.data, n_rails, rail, _u32_array(seg_ids), len(seg_ids), elem_bytes,
+                         _ptr_array(node_bufs, span, elem_bytes=elem_bytes, what="node buffer"),
                          _stream_handle(stream)))
 
 
@@ -333,3 +380,21 @@ def nz_efficiency_ratio(setup_s: Sequence[float], bytes_per_s: Sequence[float], 
     _check(lib.nz_efficiency_ratio(_models(setup_s, bytes_per_s), len(setup_s), float(msg_bytes), a,
                                    ctypes.byref(out)))
     return out.value
+
+
+NZ_HBM_REGIONS = 3
+NZ_HBM_REGION_BYTES = 96 << 30
+
+
+def nz_hbm_place(arena_bytes: int, used: np.ndarray, count: int, bytes_each: int, spread: bool,
+                 first_region: int = 0) -> np.ndarray:
+    """Offsets of ``count`` buffers inside one arena that covers HBM: spread over the three 96 GiB
+    regions (buffers that get written) or together in one region (buffers that are only read).
+    ``used`` (uint64, three counters, zeros at first) is updated in place.  Host only."""
+    lib = load()
+    if used.dtype != np.uint64 or used.shape != (NZ_HBM_REGIONS,) or not used.flags["C_CONTIGUOUS"]:
+        raise ValueError("used must be a contiguous array of three uint64 counters")
+    off = np.zeros(max(count, 1), dtype=np.uint64)
+    _check(lib.nz_hbm_place(int(arena_bytes), used.ctypes.data, int(count), int(bytes_each),
+                            1 if spread else 0, int(first_region), off.ctypes.data))
+    return off[:count]

@@ -1,36 +1,29 @@
-"""Placement of large buffers in MI355X HBM.
+"""One arena over HBM, with the buffers placed by the library's ``nz_hbm_place``.
 
-Measured on MI355X (see profiles/hbm_placement_fused_c4.txt): the 288 GiB of
-HBM3E behave as three consecutive 96 GiB regions with separate DRAM banks.  A
-streaming kernel whose *written* buffers all lie in one region is limited by
-that region's banks (the fused 32-node reduce reaches about 68 % of peak when
-its 40 GiB working set sits in one region); with the written buffers spread
-over two or three regions the same kernel reaches about 82 %.  Reads are much
-less sensitive.
-
-The library itself never allocates: where buffers live is the caller's
-decision.  This module is that decision for the harness: it takes one device
-allocation that covers (almost) all of HBM as the first large allocation of
-the process -- which the driver lays out linearly from the start of HBM -- and
-hands out tensors at chosen region offsets.
-
-Nothing here computes anything: device memory only.
+The library never allocates: where buffers live is the caller's decision.  This module is
+that decision for the harness, and nothing more than device memory handling: it takes one
+device allocation that covers (almost) all of HBM as the first large allocation of the
+process -- which the driver lays out from the start of HBM -- asks the library for offsets
+(include/nezha_sim.h explains the three 96 GiB regions and the rule), and hands out tensors
+at those offsets.  Nothing here computes anything.
 """
 from __future__ import annotations
 
 from typing import List, Optional
 
+import numpy as np
 import torch
 
+from . import nezha_sim as nz
+
 GIB = 1 << 30
-REGION_BYTES = 96 * GIB          # one third of 288 GiB
-N_REGIONS = 3
-ALIGN = 2 << 20                  # keep every buffer on a 2 MiB boundary
-EDGE_MARGIN = 1 * GIB            # stay clear of a region's ends (the boundary is known to ~1 GiB)
+REGION_BYTES = nz.NZ_HBM_REGION_BYTES
+N_REGIONS = nz.NZ_HBM_REGIONS
+ALIGN = 2 << 20
 
 
 class HbmArena:
-    """One big device allocation with a bump pointer per 96 GiB region."""
+    """One big device allocation; ``alloc`` / ``alloc_striped`` carve tensors out of it."""
 
     def __init__(self, device="cuda:0", reserve_bytes: int = 5 * GIB):
         torch.cuda.empty_cache()          # hand cached blocks back so the arena can be one allocation
@@ -44,33 +37,45 @@ class HbmArena:
         self.raw = torch.empty(size, dtype=torch.uint8, device=device)
         if self.raw.data_ptr() % ALIGN:
             raise RuntimeError("arena base is not 2 MiB aligned")
-        self._next = [k * REGION_BYTES + (EDGE_MARGIN if k else 0) for k in range(N_REGIONS)]
-        self._end = [min((k + 1) * REGION_BYTES - EDGE_MARGIN, size) for k in range(N_REGIONS)]
+        self.used = np.zeros(N_REGIONS, dtype=np.uint64)
+        self._packed_next: Optional[int] = None
 
-    def set_cursor(self, region: int, offset_bytes: int) -> None:
-        """Continue allocating in `region` from an absolute arena offset (up to the arena's end:
-        the region number then only names the cursor).  Used to place a working set at a chosen
-        distance from a region boundary."""
-        self._next[region] = (offset_bytes // ALIGN) * ALIGN
-        self._end[region] = self.size
+    def pack_from(self, offset_bytes: int) -> None:
+        """From now on hand out buffers back to back from this arena offset, whatever region
+        they fall in (used to reproduce the behaviour of a working set that lies in one region,
+        or straddles a region boundary)."""
+        self._packed_next = (offset_bytes // ALIGN) * ALIGN
 
-    def free_in(self, region: int) -> int:
-        return max(self._end[region] - self._next[region], 0)
+    def _tensors(self, offsets, n_elems: int, dtype: torch.dtype) -> List[torch.Tensor]:
+        nbytes = n_elems * torch.empty((), dtype=dtype).element_size()
+        return [self.raw[int(o):int(o) + nbytes].view(dtype) for o in offsets]
+
+    def _place(self, count: int, n_elems: int, dtype: torch.dtype, spread: bool, first: int):
+        nbytes = n_elems * torch.empty((), dtype=dtype).element_size()
+        if self._packed_next is not None:
+            rounded = -(-max(nbytes, 1) // ALIGN) * ALIGN
+            if self._packed_next + count * rounded > self.size:
+                raise RuntimeError("the arena is full")
+            offsets = [self._packed_next + i * rounded for i in range(count)]
+            self._packed_next += count * rounded
+            return self._tensors(offsets, n_elems, dtype)
+        try:
+            offsets = nz.nz_hbm_place(self.size, self.used, count, nbytes, spread, first)
+        except nz.NezhaSimError as e:
+            raise RuntimeError(f"HBM region is full ({e})") from e
+        return self._tensors(offsets, n_elems, dtype)
 
     def alloc(self, n_elems: int, dtype: torch.dtype, region: int) -> torch.Tensor:
         """A tensor of n_elems elements inside the given region (0, 1 or 2)."""
-        nbytes = n_elems * torch.empty((), dtype=dtype).element_size()
-        rounded = -(-max(nbytes, 1) // ALIGN) * ALIGN
-        if rounded > self.free_in(region):
-            raise RuntimeError(f"HBM region {region} is full")
-        off = self._next[region]
-        self._next[region] += rounded
-        return self.raw[off:off + nbytes].view(dtype)
+        return self._place(1, n_elems, dtype, False, region)[0]
 
-    def alloc_striped(self, count: int, n_elems: int, dtype: torch.dtype,
-                      regions=(0, 1, 2), start: int = 0) -> List[torch.Tensor]:
-        """`count` equal tensors, tensor i in regions[(start + i) % len(regions)]."""
-        return [self.alloc(n_elems, dtype, regions[(start + i) % len(regions)]) for i in range(count)]
+    def alloc_striped(self, count: int, n_elems: int, dtype: torch.dtype, start: int = 0) -> List[torch.Tensor]:
+        """`count` equal tensors, tensor i in region (start + i) mod 3."""
+        return self._place(count, n_elems, dtype, True, start % N_REGIONS)
+
+    def alloc_together(self, count: int, n_elems: int, dtype: torch.dtype, region: int = 0) -> List[torch.Tensor]:
+        """`count` equal tensors one after the other in one region."""
+        return self._place(count, n_elems, dtype, False, region)
 
 
 def try_arena(device="cuda:0") -> Optional[HbmArena]:

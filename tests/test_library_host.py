@@ -158,3 +158,70 @@ def test_binding_marshals_what_the_header_declares():
         want = [k for k in (kind(p) for p in params.split(",")) if k]
         got = [ctype_kind[t] for t in getattr(lib, name).argtypes]
         assert got == want, name
+
+
+def test_binding_refuses_tensors_the_kernels_could_not_trust():
+    """The binding checks a tensor before it hands its address to the library: host tensors,
+    non-contiguous views, a wrong element type and buffers shorter than the call says are
+    refused with ValueError, before any library call."""
+    import torch
+    good = [torch.zeros(8) for _ in range(2)]
+    with pytest.raises(ValueError, match="not a device tensor"):
+        nz.nz_allreduce_sim(good, 8, (1,), "f32", "fused", good)
+
+    class FakeDevice:
+        """Stands in for a device tensor (no GPU here): only what the checks look at."""
+        def __init__(self, n, dtype=torch.float32, contiguous=True):
+            self.is_cuda, self.dtype, self._n, self._c = True, dtype, n, contiguous
+        def is_contiguous(self): return self._c
+        def element_size(self): return torch.empty((), dtype=self.dtype).element_size()
+        def numel(self): return self._n
+        def data_ptr(self): raise AssertionError("address taken from a rejected tensor")
+
+    for bad, text in ((FakeDevice(8, contiguous=False), "not contiguous"),
+                      (FakeDevice(8, dtype=torch.int32), "dtype"),
+                      (FakeDevice(7), "holds 7 elements")):
+        with pytest.raises(ValueError, match=text):
+            nz.nz_allreduce_sim([bad, bad], 8, (1,), "f32", "fused", [bad, bad])
+    seg = nz.nz_segment_map(nz.nz_rail_partition(64, 4, (1,)), 2)
+    with pytest.raises(ValueError, match="4-byte elements|2-byte elements"):
+        nz.nz_pack([FakeDevice(64, dtype=torch.float16)] * 2, seg, 0, [0, 1], 4, [FakeDevice(64)] * 2, 256)
+    with pytest.raises(ValueError, match="holds 10 elements"):
+        nz.nz_unpack([FakeDevice(10)] * 2, seg, 0, [0, 1], 4, [FakeDevice(64)] * 2)
+
+
+def test_hbm_place_spreads_written_buffers_and_keeps_read_buffers_together():
+    """nz_hbm_place is pure host arithmetic: offsets are 2 MiB multiples, disjoint, inside the
+    region asked for (a margin away from region boundaries), written buffers rotate over the
+    three regions, and a request that does not fit changes nothing."""
+    GIB, R = 1 << 30, nz.NZ_HBM_REGION_BYTES
+    arena = 283 * GIB
+    used = np.zeros(3, dtype=np.uint64)
+    each = 670_000_000
+    ins = nz.nz_hbm_place(arena, used, 32, each, False, 0)
+    outs = nz.nz_hbm_place(arena, used, 32, each, True, 0)
+    send = nz.nz_hbm_place(arena, used, 32, 536_000_000, True, 1)
+    taken = []
+    for group, size in ((ins, each), (outs, each), (send, 536_000_000)):
+        for o in group:
+            o = int(o)
+            assert o % (2 << 20) == 0 and o + size <= arena
+            r = o // R
+            assert (o - r * R >= GIB or r == 0) and (r + 1) * R - (o + size) >= GIB   # the margin
+            taken.append((o, o + size))
+    taken.sort()
+    assert all(a[1] <= b[0] for a, b in zip(taken, taken[1:]))
+    assert {int(o) // R for o in ins} == {0}
+    assert [int(o) // R for o in outs[:6]] == [0, 1, 2, 0, 1, 2]
+    assert [int(o) // R for o in send[:4]] == [1, 2, 0, 1]
+    before = used.copy()
+    with pytest.raises(nz.NezhaSimError) as ex:
+        nz.nz_hbm_place(arena, used, 200, each, False, 1)        # 125 GiB into one region
+    assert ex.value.status == 4 and np.array_equal(used, before)
+    with pytest.raises(nz.NezhaSimError) as ex:
+        nz.nz_hbm_place(arena, used, 1, each, True, 3)
+    assert ex.value.status == 1
+    small = np.zeros(3, dtype=np.uint64)
+    with pytest.raises(nz.NezhaSimError):                          # an arena that ends inside region 0's margin of region 1
+        nz.nz_hbm_place(90 * GIB, small, 1, each, False, 1)
+    assert list(nz.nz_hbm_place(90 * GIB, small, 2, each, False, 0)) == [0, 640 << 20]
