@@ -200,9 +200,12 @@ def size_sweep(torch, nz, dev, use_graph: bool = False) -> int:
         for log2 in range(11, 27):
             S = 1 << log2
             n = S // 4
-            ins = [torch.randn(n, device=dev) * 1e-2 for _ in range(N)]
-            outs = [torch.empty_like(t) for t in ins]
+            ins_t = [torch.randn(n, device=dev) * 1e-2 for _ in range(N)]
+            outs_t = [torch.empty_like(t) for t in ins_t]
+            # checked once, used by every call of this size (what a caller in a loop does)
+            ins, outs = nz.BufferTable(ins_t, "f32"), nz.BufferTable(outs_t, "f32")
             row = {"n_nodes": N, "msg_bytes": S}
+            st = None if use_graph else torch.cuda.current_stream().cuda_stream     # the raw stream handle
             for mode in ("fused", "ring-stepwise"):
                 reps = 200 if S <= (1 << 22) else 30
                 for _ in range(5):
@@ -222,7 +225,7 @@ def size_sweep(torch, nz, dev, use_graph: bool = False) -> int:
                 else:
                     a.record()
                     for _ in range(reps):
-                        nz.nz_allreduce_sim(ins, n, (1, 1), "f32", mode, outs)
+                        nz.nz_allreduce_sim(ins, n, (1, 1), "f32", mode, outs, st)
                     b.record()
                 torch.cuda.synchronize()
                 us = a.elapsed_time(b) * 1e3 / reps

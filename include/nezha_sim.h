@@ -120,15 +120,16 @@ nz_status nz_segment_map(const uint64_t *rail_off, uint32_t n_rails, uint32_t n_
  *   NZ_FUSED: every element is read once from all nodes, summed in fp32
  *     registers (int32: wrapping integer add) in a fixed blocked pairwise
  *     order that depends on n_nodes only, rounded once to `dtype` (nearest
- *     even) and written once to every distinct output buffer.  Up to 48 MiB
- *     per node, or with a single distinct output buffer, this is one launch
- *     whose unit of work is a tile of a segment.  Larger messages with
- *     several output buffers run as a short pipeline of launches over pieces
- *     of at most 24 MiB of the participating rails: launch c sums piece c
- *     into the first distinct output buffer and copies piece c - 1 from there
- *     (re-read through the L2 caches) to the other output buffers one after
- *     the other, because a single write stream at a time is what HBM sustains
- *     best.  The result is bitwise the same either way.
+ *     even) and written once to every distinct output buffer.  With a
+ *     single distinct output buffer, or while the outputs together take
+ *     less than 128 MiB, this is one launch whose unit of work is a tile
+ *     of a segment.  Larger jobs run as a short pipeline of launches over
+ *     pieces of at most 24 MiB of the participating rails: launch c sums
+ *     piece c into one of the output buffers (the one farthest from the
+ *     inputs) and copies piece c - 1 from there (re-read through the L2
+ *     caches) to the other output buffers one after the other, because a
+ *     single write stream at a time is what HBM sustains best.  The result
+ *     is bitwise the same either way.
  *   NZ_RING_STEPWISE: 2 (n_nodes - 1) launches, one per ring step, in stream
  *     order.  Node r sends to node (r+1) mod N; in reduce-scatter step s it
  *     sends segment (r - s) mod N and the receiver stores

@@ -345,13 +345,14 @@ struct FusedArgs {
 // fp32 error stays below 8 * 2^-24 * sum|x|, and the eight loads of a block
 // are independent and in flight together.
 // Sum of a full block of eight nodes starting at node m0: a balanced tree.
-template <class T, class P>
+template <class T, class P, bool CACHED>
 __device__ __forceinline__ void block_sum8(NodeTable in, u32 m0, u64 byte_off,
                                            typename T::acc_t (&s)[P::kLanes])
 {
     typename P::raw_t r[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) r[i] = P::load(in[m0 + i], byte_off);
+    for (int i = 0; i < 8; ++i)
+        r[i] = CACHED ? P::load_again(in[m0 + i], byte_off) : P::load(in[m0 + i], byte_off);
 #pragma unroll
     for (int l = 0; l < P::kLanes; ++l)
         s[l] = ((P::lane(r[0], l) + P::lane(r[1], l)) + (P::lane(r[2], l) + P::lane(r[3], l))) +
@@ -360,14 +361,17 @@ __device__ __forceinline__ void block_sum8(NodeTable in, u32 m0, u64 byte_off,
 
 // Sum of the last, partial block (1 <= nb <= 7 nodes): the same tree with the
 // missing leaves left out.
-template <class T, class P>
+template <class T, class P, bool CACHED>
 __device__ __forceinline__ void block_sum_tail(NodeTable in, u32 m0, u32 nb, u64 byte_off,
                                                typename T::acc_t (&s)[P::kLanes])
 {
     typedef typename T::acc_t acc_t;
     typename P::raw_t r[7];
 #pragma unroll
-    for (int i = 0; i < 7; ++i) r[i] = P::load(in[(u32)i < nb ? m0 + i : m0], byte_off);
+    for (int i = 0; i < 7; ++i) {
+        const void *src = in[(u32)i < nb ? m0 + i : m0];
+        r[i] = CACHED ? P::load_again(src, byte_off) : P::load(src, byte_off);
+    }
 #pragma unroll
     for (int l = 0; l < P::kLanes; ++l) {
         const acc_t p0 = nb > 1 ? P::lane(r[0], l) + P::lane(r[1], l) : P::lane(r[0], l);
@@ -392,18 +396,21 @@ enum NodeClass {
 };
 
 // One block's sum, full or partial: block number blk of n_full full blocks.
-template <class T, class P>
+template <class T, class P, bool CACHED>
 __device__ __forceinline__ void block_sum(NodeTable in, u32 blk, u32 n_full, u32 n_tail, u64 byte_off,
                                           typename T::acc_t (&s)[P::kLanes])
 {
     if (blk < n_full)
-        block_sum8<T, P>(in, blk * 8, byte_off, s);
+        block_sum8<T, P, CACHED>(in, blk * 8, byte_off, s);
     else
-        block_sum_tail<T, P>(in, blk * 8, n_tail, byte_off, s);
+        block_sum_tail<T, P, CACHED>(in, blk * 8, n_tail, byte_off, s);
 }
 
-// The sum at one packet position, narrowed to the storage type.
-template <class T, class P, int CLASS>
+// The sum at one packet position, narrowed to the storage type.  CACHED: the
+// job is small enough to live in the last-level cache (the gradients were
+// just written by the kernels before, the sums are read by the kernels after),
+// so ordinary cache-allocating accesses are used instead of streaming ones.
+template <class T, class P, int CLASS, bool CACHED>
 __device__ __forceinline__ typename P::raw_t reduce_at(NodeTable in, u32 N, u64 byte_off)
 {
     typedef typename T::acc_t acc_t;
@@ -411,17 +418,17 @@ __device__ __forceinline__ typename P::raw_t reduce_at(NodeTable in, u32 N, u64 
     acc_t res[L];
     if (CLASS == kUpTo8) {
         if (N == 8)
-            block_sum8<T, P>(in, 0, byte_off, res);
+            block_sum8<T, P, CACHED>(in, 0, byte_off, res);
         else
-            block_sum_tail<T, P>(in, 0, N, byte_off, res);
+            block_sum_tail<T, P, CACHED>(in, 0, N, byte_off, res);
         return P::narrow(res);
     }
     if (CLASS == kUpTo32) {
         const u32 n_full = N >> 3, n_tail = N & 7u, n_blocks = n_full + (n_tail ? 1u : 0u);
-        block_sum<T, P>(in, 0, n_full, n_tail, byte_off, res);
+        block_sum<T, P, CACHED>(in, 0, n_full, n_tail, byte_off, res);
         if (n_blocks > 1) {
             acc_t s[L];
-            block_sum<T, P>(in, 1, n_full, n_tail, byte_off, s);
+            block_sum<T, P, CACHED>(in, 1, n_full, n_tail, byte_off, s);
 #pragma unroll
             for (int l = 0; l < L; ++l) res[l] = res[l] + s[l];
         }
@@ -429,12 +436,12 @@ __device__ __forceinline__ typename P::raw_t reduce_at(NodeTable in, u32 N, u64 
 #pragma unroll
             for (int l = 0; l < L; ++l) asm volatile("" : "+v"(res[l]) : : "memory");
             acc_t u[L];
-            block_sum<T, P>(in, 2, n_full, n_tail, byte_off, u);
+            block_sum<T, P, CACHED>(in, 2, n_full, n_tail, byte_off, u);
             if (n_blocks > 3) {
 #pragma unroll
                 for (int l = 0; l < L; ++l) asm volatile("" : "+v"(u[l]) : : "memory");
                 acc_t s[L];
-                block_sum<T, P>(in, 3, n_full, n_tail, byte_off, s);
+                block_sum<T, P, CACHED>(in, 3, n_full, n_tail, byte_off, s);
 #pragma unroll
                 for (int l = 0; l < L; ++l) u[l] = u[l] + s[l];
             }
@@ -450,7 +457,7 @@ __device__ __forceinline__ typename P::raw_t reduce_at(NodeTable in, u32 N, u64 
         for (int c = 0; c < 4; ++c) {
             if (b + c >= n_full) break;
             acc_t s[L];
-            block_sum8<T, P>(in, (b + c) * 8, byte_off, s);
+            block_sum8<T, P, CACHED>(in, (b + c) * 8, byte_off, s);
 #pragma unroll
             for (int l = 0; l < L; ++l) run[c][l] = (b == 0) ? s[l] : run[c][l] + s[l];
             // One block's eight loads in flight at a time: the running sum is
@@ -465,7 +472,7 @@ __device__ __forceinline__ typename P::raw_t reduce_at(NodeTable in, u32 N, u64 
     if (n_tail) {
         // The partial block is block number n_full: it goes to running sum n_full mod 4.
         acc_t s[L];
-        block_sum_tail<T, P>(in, n_full * 8, n_tail, byte_off, s);
+        block_sum_tail<T, P, CACHED>(in, n_full * 8, n_tail, byte_off, s);
         const u32 slot = n_full & 3u;
         const bool first = n_full < 4;
 #pragma unroll
@@ -492,15 +499,18 @@ __device__ __forceinline__ typename P::raw_t reduce_at(NodeTable in, u32 N, u64 
 // Reduce one packet position and store it to out[out_begin .. out_end).  The
 // stores start at a buffer that depends on the workgroup, so that workgroups
 // running at the same time write to different buffers.
-template <class T, class P, int CLASS>
+template <class T, class P, int CLASS, bool CACHED>
 __device__ __forceinline__ void reduce_bcast_at(const NZ_KARG FusedArgs &a, u64 byte_off, u32 out_begin,
                                                 u32 out_end)
 {
-    const typename P::raw_t packed = reduce_at<T, P, CLASS>(a.in, a.g.n_nodes, byte_off);
+    const typename P::raw_t packed = reduce_at<T, P, CLASS, CACHED>(a.in, a.g.n_nodes, byte_off);
     const u32 K = out_end - out_begin;
     u32 o = out_begin + blockIdx.x % K;
     for (u32 i = 0; i < K; ++i) {
-        P::store(a.out[o], byte_off, packed);
+        if (CACHED)
+            P::store_for_reuse(a.out[o], byte_off, packed);
+        else
+            P::store(a.out[o], byte_off, packed);
         if (++o == out_end) o = out_begin;
     }
 }
@@ -510,7 +520,7 @@ __device__ __forceinline__ void reduce_bcast_at(const NZ_KARG FusedArgs &a, u64 
 // vectors that lie wholly inside it.  They are followed by one workgroup per
 // (rail, segment) for the elements that share a 16-byte vector with a
 // neighbouring segment or with the end of the buffer: one thread per element.
-template <class T, int CLASS>
+template <class T, int CLASS, bool CACHED>
 __global__ __launch_bounds__(kThreads) void nz_fused_reduce_bcast(const FusedArgs)
 {
     const NZ_KARG FusedArgs &a = kernel_args<FusedArgs>();
@@ -525,7 +535,7 @@ __global__ __launch_bounds__(kThreads) void nz_fused_reduce_bcast(const FusedArg
         const u64 vec = t.tile_base + threadIdx.x;
         const u32 owner = (seg == 0 ? a.g.n_nodes : seg) - 1;
         const u32 o0 = a.owner_only ? owner : 0, o1 = a.owner_only ? owner + 1 : a.n_out;
-        if (vec >= lo && vec < hi) reduce_bcast_at<T, VecPacket<T>, CLASS>(a, vec << 4, o0, o1);
+        if (vec >= lo && vec < hi) reduce_bcast_at<T, VecPacket<T>, CLASS, CACHED>(a, vec << 4, o0, o1);
         return;
     }
     const u32 e = blockIdx.x - n_tiles;
@@ -541,9 +551,9 @@ __global__ __launch_bounds__(kThreads) void nz_fused_reduce_bcast(const FusedArg
     const u64 eoff = (u64)lane << T::kShift;
     const u32 owner = (seg == 0 ? a.g.n_nodes : seg) - 1;
     const u32 o0 = a.owner_only ? owner : 0, o1 = a.owner_only ? owner + 1 : a.n_out;
-    if (part == 0 && t.b0 + eoff < head_end) reduce_bcast_at<T, ElemPacket<T>, CLASS>(a, t.b0 + eoff, o0, o1);
+    if (part == 0 && t.b0 + eoff < head_end) reduce_bcast_at<T, ElemPacket<T>, CLASS, CACHED>(a, t.b0 + eoff, o0, o1);
     if (part == 1 && tail_beg + eoff < t.b1)
-        reduce_bcast_at<T, ElemPacket<T>, CLASS>(a, tail_beg + eoff, o0, o1);
+        reduce_bcast_at<T, ElemPacket<T>, CLASS, CACHED>(a, tail_beg + eoff, o0, o1);
 }
 
 // ---------------------------------------------------------------------------
@@ -592,11 +602,11 @@ __global__ __launch_bounds__(kThreads) void nz_fused_stage(const StageArgs)
     if (blockIdx.x < a.n_a_blocks) {
         const u64 b0 = a.a_lo + (((u64)blockIdx.x * kThreads + threadIdx.x) << 4);
         if (b0 + 16 <= a.a_hi) {
-            VecPacket<T>::store(a.out[0], b0, reduce_at<T, VecPacket<T>, CLASS>(a.in, a.n_nodes, b0));
+            VecPacket<T>::store(a.out[0], b0, reduce_at<T, VecPacket<T>, CLASS, false>(a.in, a.n_nodes, b0));
         } else if (b0 < a.a_hi) {
             // the end of the message inside a vector: element by element
             for (u64 b = b0; b < a.a_hi; b += sizeof(typename T::elem_t))
-                ElemPacket<T>::store(a.out[0], b, reduce_at<T, ElemPacket<T>, CLASS>(a.in, a.n_nodes, b));
+                ElemPacket<T>::store(a.out[0], b, reduce_at<T, ElemPacket<T>, CLASS, false>(a.in, a.n_nodes, b));
         }
         return;
     }

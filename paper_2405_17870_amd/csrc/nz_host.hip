@@ -103,22 +103,39 @@ u64 build_geometry(RailGeom &g, const u64 *rail_off, u32 n_rails, u32 n_nodes, u
     return total == 0 ? kNothingToDo : total;
 }
 
-template <class T>
-nz_status launch_fused(const FusedArgs &a, u32 blocks, hipStream_t st)
+// Bytes a single-launch fused call moves up to which it uses cache-allocating
+// accesses (half of the 256 MB last-level cache): a job of that size finds its
+// inputs in cache and leaves its results there for whoever reads them next.
+constexpr u64 kFusedCachedBytes = 128ull << 20;
+
+template <class T, bool CACHED>
+hipError_t launch_fused_class(const FusedArgs &a, u32 blocks, hipStream_t st)
 {
-    const hipError_t e = a.g.n_nodes <= 8    ? launch(nz_fused_reduce_bcast<T, kUpTo8>, blocks, a, st)
-                         : a.g.n_nodes <= 32 ? launch(nz_fused_reduce_bcast<T, kUpTo32>, blocks, a, st)
-                                             : launch(nz_fused_reduce_bcast<T, kAnyN>, blocks, a, st);
+    return a.g.n_nodes <= 8    ? launch(nz_fused_reduce_bcast<T, kUpTo8, CACHED>, blocks, a, st)
+           : a.g.n_nodes <= 32 ? launch(nz_fused_reduce_bcast<T, kUpTo32, CACHED>, blocks, a, st)
+                               : launch(nz_fused_reduce_bcast<T, kAnyN, CACHED>, blocks, a, st);
+}
+
+template <class T>
+nz_status launch_fused(const FusedArgs &a, u32 blocks, hipStream_t st, u64 moved_bytes)
+{
+    const hipError_t e = moved_bytes <= kFusedCachedBytes ? launch_fused_class<T, true>(a, blocks, st)
+                                                          : launch_fused_class<T, false>(a, blocks, st);
     return e == hipSuccess ? NZ_OK : hip_failed(e, "fused reduce launch");
 }
 
 // Payload per node from which the fused allreduce with several output buffers
-// is issued as the staged pipeline (see nz_fused_stage); below it the single
-// launch is faster.
+// is issued as the staged pipeline (see nz_fused_stage) ...
 #ifndef NZ_STAGE_MIN_BYTES
-#define NZ_STAGE_MIN_BYTES (8ull << 20)
+#define NZ_STAGE_MIN_BYTES (1ull << 20)
 #endif
 constexpr u64 kStageMinBytes = NZ_STAGE_MIN_BYTES;
+// ... and the bytes written to all outputs together (measured on plain
+// allocations: 32 outputs win from 4 MB per node, 8 outputs from 16 MB).
+#ifndef NZ_STAGE_MIN_OUTPUT_BYTES
+#define NZ_STAGE_MIN_OUTPUT_BYTES (128ull << 20)
+#endif
+constexpr u64 kStageMinOutputBytes = NZ_STAGE_MIN_OUTPUT_BYTES;
 // A message shorter than one full piece is still cut into this many pieces (of
 // at least kStageSmallestPiece bytes), so that its reduce and spread parts overlap.
 #ifndef NZ_STAGE_MIN_PIECES
@@ -490,7 +507,8 @@ nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t
         u64 active_bytes = 0;
         for (u32 k = 0; k < n_rails; ++k)
             if (rail_mask >> k & 1u) active_bytes += (rail_off[k + 1] - rail_off[k]) << shift;
-        if (what == kAllreduce && a.n_out >= 2 && active_bytes >= kStageMinBytes) {
+        if (what == kAllreduce && a.n_out >= 2 && active_bytes >= kStageMinBytes &&
+            active_bytes * a.n_out >= kStageMinOutputBytes) {
             // Large message, several outputs: the staged pipeline.
             StageArgs sa;
             std::memset(&sa, 0, sizeof sa);
@@ -498,6 +516,30 @@ nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t
             sa.n_out = a.n_out;
             for (u32 i = 0; i < n_nodes; ++i) sa.in[i] = a.in[i];
             for (u32 i = 0; i < a.n_out; ++i) sa.out[i] = a.out[i];
+            // The sums are staged through the output that lies farthest from the
+            // inputs: a write stream into the memory region the reduce part is
+            // reading from slows those reads down, and under a layout that
+            // spreads the outputs (nz_hbm_place) the farthest one is in another
+            // region.  Which output comes first changes no result.
+            {
+                uintptr_t in_lo = UINTPTR_MAX, in_hi = 0;
+                for (u32 i = 0; i < n_nodes; ++i) {
+                    const uintptr_t p = reinterpret_cast<uintptr_t>(a.in[i]);
+                    in_lo = std::min(in_lo, p);
+                    in_hi = std::max(in_hi, p + bytes);
+                }
+                u32 best = 0;
+                uintptr_t best_gap = 0;
+                for (u32 o = 0; o < a.n_out; ++o) {
+                    const uintptr_t p = reinterpret_cast<uintptr_t>(a.out[o]);
+                    const uintptr_t gap = p >= in_hi ? p - in_hi : (p + bytes <= in_lo ? in_lo - (p + bytes) : 0);
+                    if (gap > best_gap) {
+                        best_gap = gap;
+                        best = o;
+                    }
+                }
+                std::swap(sa.out[0], sa.out[best]);
+            }
             switch (dtype) {
             case NZ_F32: return launch_staged<TF32>(sa, rail_off, n_rails, rail_mask, shift, st);
             case NZ_I32: return launch_staged<TI32>(sa, rail_off, n_rails, rail_mask, shift, st);
@@ -510,11 +552,12 @@ nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t
         if (blocks == 0) return NZ_ERR_UNSUPPORTED;
         if (blocks == kNothingToDo) return NZ_OK;
         blocks += (u64)n_rails * n_nodes;  // the workgroups for segment edges
+        const u64 moved = active_bytes * (n_nodes + (a.owner_only ? 1 : a.n_out));
         switch (dtype) {
-        case NZ_F32: return launch_fused<TF32>(a, (u32)blocks, st);
-        case NZ_I32: return launch_fused<TI32>(a, (u32)blocks, st);
-        case NZ_BF16: return launch_fused<TBF16>(a, (u32)blocks, st);
-        case NZ_F16: return launch_fused<TF16>(a, (u32)blocks, st);
+        case NZ_F32: return launch_fused<TF32>(a, (u32)blocks, st, moved);
+        case NZ_I32: return launch_fused<TI32>(a, (u32)blocks, st, moved);
+        case NZ_BF16: return launch_fused<TBF16>(a, (u32)blocks, st, moved);
+        case NZ_F16: return launch_fused<TF16>(a, (u32)blocks, st, moved);
         }
         return NZ_ERR_INVALID_ARG;
     }
@@ -587,7 +630,7 @@ nz_status nz_allreduce_launches(uint32_t n_nodes, uint64_t n_elems, const uint32
         return NZ_OK;
     }
     const u64 bytes = n_elems * eb;
-    if (n_distinct_outputs < 2 || bytes < kStageMinBytes) {
+    if (n_distinct_outputs < 2 || bytes < kStageMinBytes || bytes * n_distinct_outputs < kStageMinOutputBytes) {
         *launches = 1;
         return NZ_OK;
     }

@@ -59,7 +59,9 @@ def load() -> ctypes.CDLL:
         raise RuntimeError(
             f"{LIB_PATH} is missing: build it first (python -m paper_2405_17870_amd.build "
             "or __graft_entry__.build()); there is no fallback path")
-    import torch  # noqa: F401  -- loads the HIP runtime this library must share with torch
+    import torch  # loads the HIP runtime this library must share with torch
+    _TORCH_DTYPE.update({"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16,
+                         "i32": torch.int32})
     lib = ctypes.CDLL(LIB_PATH)
     u64, u32, vp, i32 = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_int
     lib.nz_status_str.argtypes = [i32]
@@ -110,16 +112,44 @@ def _check(status: int) -> None:
         raise NezhaSimError(status, text + (f" ({hip})" if status == 5 and hip else ""))
 
 
+_u32_cache = {}
+
+
 def _u32_array(values: Sequence[int]):
+    """A ctypes array of unsigned 32-bit values; arrays of short tuples (rail weights, segment
+    lists) are kept, since callers pass the same ones again and again."""
+    key = tuple(values) if len(values) <= 16 else None
+    if key is not None:
+        hit = _u32_cache.get(key)
+        if hit is not None:
+            return hit
     vals = [int(v) for v in values]
     for v in vals:
         if v < 0 or v > 0xFFFFFFFF:
             raise ValueError("value does not fit an unsigned 32-bit integer")
-    return (ctypes.c_uint32 * max(len(vals), 1))(*vals)
+    arr = (ctypes.c_uint32 * max(len(vals), 1))(*vals)
+    if key is not None and len(_u32_cache) < 1024:
+        _u32_cache[key] = arr
+    return arr
 
 
-_TORCH_DTYPE_NAME = {"f32": "torch.float32", "bf16": "torch.bfloat16", "f16": "torch.float16",
-                     "i32": "torch.int32"}
+_TORCH_DTYPE = {}          # dtype string -> torch dtype, filled by load()
+
+
+class BufferTable:
+    """A host array of device addresses that has been checked once and can be handed to any
+    number of calls (the per-call cost of checking 2 N tensors is what a small allreduce
+    notices).  Keeps the tensors alive.  ``n_elems`` is what every buffer is known to hold."""
+
+    def __init__(self, tensors, dtype: Optional[str] = None, elem_bytes: Optional[int] = None,
+                 what: str = "buffer"):
+        self.tensors = list(tensors)
+        self.dtype, self.elem_bytes = dtype, elem_bytes
+        self.n_elems = min((t.numel() for t in self.tensors if hasattr(t, "numel")), default=0)
+        self.array = _ptr_array(self.tensors, 0, dtype, elem_bytes, what)
+
+    def __len__(self):
+        return len(self.tensors)
 
 
 def _ptr_array(tensors, min_elems: int = 0, dtype: Optional[str] = None,
@@ -127,8 +157,16 @@ def _ptr_array(tensors, min_elems: int = 0, dtype: Optional[str] = None,
     """Host array of device addresses.  A torch tensor is checked before its address is taken --
     on the device, contiguous, of the stated element type (or element size) and holding at
     least ``min_elems`` elements -- because the kernels trust these facts; a raw integer
-    address is passed through as it is."""
+    address is passed through as it is.  A BufferTable was checked when it was made."""
+    if isinstance(tensors, BufferTable):
+        if dtype is not None and tensors.dtype is not None and tensors.dtype != dtype:
+            raise ValueError(f"{what} table was made for {tensors.dtype}, the call says {dtype}")
+        if tensors.n_elems < min_elems and any(hasattr(t, "numel") for t in tensors.tensors):
+            raise ValueError(f"{what} table holds {tensors.n_elems} elements per buffer, the call needs {min_elems}")
+        return tensors.array
     arr = (ctypes.c_void_p * max(len(tensors), 1))()
+    want = _TORCH_DTYPE.get(dtype) if dtype is not None else None
+    check_size = elem_bytes in (2, 4)          # other sizes: the library refuses
     for i, t in enumerate(tensors):
         if not hasattr(t, "data_ptr"):
             arr[i] = int(t)
@@ -137,9 +175,9 @@ def _ptr_array(tensors, min_elems: int = 0, dtype: Optional[str] = None,
             raise ValueError(f"{what} {i} is not a device tensor")
         if not t.is_contiguous():
             raise ValueError(f"{what} {i} is not contiguous")
-        if dtype is not None and str(t.dtype) != _TORCH_DTYPE_NAME[dtype]:
+        if want is not None and t.dtype is not want:
             raise ValueError(f"{what} {i} has dtype {t.dtype}, the call says {dtype}")
-        if elem_bytes in (2, 4) and t.element_size() != elem_bytes:     # other sizes: the library refuses
+        if check_size and t.element_size() != elem_bytes:
             raise ValueError(f"{what} {i} has {t.element_size()}-byte elements, the call says {elem_bytes}")
         if t.numel() < min_elems:
             raise ValueError(f"{what} {i} holds {t.numel()} elements, the call needs {min_elems}")
@@ -148,8 +186,11 @@ def _ptr_array(tensors, min_elems: int = 0, dtype: Optional[str] = None,
 
 
 def _stream_handle(stream) -> ctypes.c_void_p:
-    import torch
+    """A torch stream, a raw hipStream_t as an integer, or None for torch's current stream."""
+    if isinstance(stream, int):
+        return ctypes.c_void_p(stream)
     if stream is None:
+        import torch
         stream = torch.cuda.current_stream()
     return ctypes.c_void_p(stream.cuda_stream)
 
