@@ -136,14 +136,6 @@ constexpr u64 kStageMinBytes = NZ_STAGE_MIN_BYTES;
 #define NZ_STAGE_MIN_OUTPUT_BYTES (128ull << 20)
 #endif
 constexpr u64 kStageMinOutputBytes = NZ_STAGE_MIN_OUTPUT_BYTES;
-// A message shorter than one full piece is still cut into this many pieces (of
-// at least kStageSmallestPiece bytes), so that its reduce and spread parts overlap.
-#ifndef NZ_STAGE_MIN_PIECES
-#define NZ_STAGE_MIN_PIECES 1
-#endif
-constexpr u64 kStageMinPieces = NZ_STAGE_MIN_PIECES;
-constexpr u64 kStageSmallestPiece = 2ull << 20;
-
 u64 round_up(u64 x, u64 m) { return (x + m - 1) / m * m; }
 
 template <class T>
@@ -185,9 +177,7 @@ nz_status launch_staged(StageArgs &a, const u64 *rail_off, u32 n_rails, u32 rail
         const u64 lo = rail_off[k] << elem_shift, hi = rail_off[end] << elem_shift;
         k = end;
         if (hi == lo) continue;
-        u64 n_pieces = (hi - lo + kStagePieceBytes - 1) / kStagePieceBytes;
-        n_pieces = std::max<u64>(n_pieces, std::min<u64>(kStageMinPieces, (hi - lo) / kStageSmallestPiece));
-        if (n_pieces == 0) n_pieces = 1;
+        const u64 n_pieces = (hi - lo + kStagePieceBytes - 1) / kStagePieceBytes;
         const u64 piece = round_up((hi - lo + n_pieces - 1) / n_pieces, (u64)kThreads * 16);
         for (u64 p = lo; p < hi; p += piece) {
             a.a_lo = p;

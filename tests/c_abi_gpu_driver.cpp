@@ -102,6 +102,19 @@ extern "C" int nz_c_abi_checks(void)
         std::vector<int32_t> expect(n, 0x7fffffff);
         if (allreduce_case("fingerprints", st, N, n, ratios, 3, NZ_I32, in, expect)) return 1;
     }
+    // 2b. the same fingerprints at a size whose fused form is the pipeline of launches
+    //     (31 outputs x 4.5 MB > 128 MiB), checked through the launch count and bit by bit
+    {
+        const uint32_t N = 31, ratios[2] = {100, 25};
+        const uint64_t n = 1123457;
+        uint64_t launches = 0;
+        REQUIRE(nz_allreduce_launches(N, n, ratios, 2, NZ_I32, NZ_FUSED, N, &launches) == NZ_OK && launches > 1);
+        REQUIRE(nz_allreduce_launches(N, n, ratios, 2, NZ_I32, NZ_FUSED, 1, &launches) == NZ_OK && launches == 1);
+        std::vector<std::vector<int32_t>> in(N);
+        for (uint32_t i = 0; i < N; ++i) in[i].assign(n, (int32_t)(1u << i));
+        std::vector<int32_t> expect(n, 0x7fffffff);
+        if (allreduce_case("fingerprints, staged", st, N, n, ratios, 2, NZ_I32, in, expect)) return 1;
+    }
     // 3. two nodes, fp32: the result is one IEEE addition, whatever the mode
     {
         const uint32_t N = 2, ratios[2] = {3, 1};
