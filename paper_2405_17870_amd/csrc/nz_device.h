@@ -764,39 +764,102 @@ __global__ __launch_bounds__(kThreads) void nz_ring_wave(const RingWaveArgs)
 
 // Direct allgather: every segment is read from the node that owns it after a
 // reduce-scatter, node (j - 1) mod N for segment j, and stored to the other
-// N - 1 nodes' buffers.
+// N - 1 nodes' buffers.  Two kernels.
 //
-// Long segments go one destination buffer after the other, because one write
-// stream at a time is what the memory system handles best: a segment is
-// worked on in pieces small enough for the L2 caches (g.win_len elements;
-// g.tps workgroups per piece, a multiple of 8, so that a tile is always
-// copied by the same XCD); the first destination's pass brings the piece into
-// L2, the other N - 2 passes read it there.  Short segments (a piece is gone
-// before a second workgroup wave could follow it) are read once and stored to
-// all destinations by the same workgroup.  grp[k] is the number of
-// destinations a workgroup of rail k serves: 1 or N - 1.  Workgroup order
-// within a rail: segment, piece, destination group, tile.  A pure copy, so T
-// only fixes the element size of the edge path.
+// nz_gather_range (segments of at least one tile): one destination buffer
+// after the other, because one write stream at a time is what the memory
+// system handles best.  A rail's range is worked on in pieces small enough
+// for the L2 caches, whatever segments they span: for every piece, for every
+// destination d, the piece is copied into d's buffer from the owners of the
+// segments it covers (d keeps the segment it owns).  The first destination's
+// pass brings the piece into L2, the other passes read it there; a piece has
+// a multiple of 8 workgroups, so that a tile is always copied by the same
+// XCD.  Workgroup order within a rail: piece, destination, tile.  A tile is
+// shorter than a segment, so it meets at most one segment boundary, which the
+// workgroup locates once; a vector that the boundary (or the end of the
+// message) cuts is copied element by element.
+struct GatherRangeArgs {
+    RailGeom g;                     // tps = workgroups per piece, win_* unused
+    u32 pieces[NZ_MAX_RAILS];       // pieces per rail
+    void *buf[NZ_MAX_NODES];
+};
+
+template <class T, int ITERS>
+__global__ __launch_bounds__(kThreads) void nz_gather_range(const GatherRangeArgs)
+{
+    const NZ_KARG GatherRangeArgs &a = kernel_args<GatherRangeArgs>();
+    constexpr int TILE = ITERS * kThreads;
+    typedef typename T::elem_t elem_t;
+    const u32 N = a.g.n_nodes;
+    u32 rail = 0;
+    while (rail + 1 < a.g.n_rails && blockIdx.x >= a.g.tile0[rail + 1]) ++rail;
+    const u32 tps = a.g.tps[rail];
+    u32 rest = blockIdx.x - a.g.tile0[rail];
+    const u32 tile = rest % tps;
+    rest /= tps;
+    const u32 d = rest % N, piece = rest / N;
+    const u64 r0 = a.g.off[rail] << T::kShift, r1 = a.g.off[rail + 1] << T::kShift;  // the rail in bytes
+    const u64 v0 = (r0 >> 4) + ((u64)piece * tps + tile) * TILE;
+    if ((v0 << 4) >= r1) return;
+
+    // The segment the tile starts in, and where the next one begins (elements).
+    const u64 q = a.g.q[rail], rem = a.g.rem[rail];
+    const u64 x_rel = ((v0 << 4) - r0) >> T::kShift, longer = rem * (q + 1);
+    const u32 j0 = (u32)(x_rel < longer ? x_rel / (q + 1) : rem + (x_rel - longer) / q);
+    const u64 bnd = a.g.off[rail] + (u64)(j0 + 1) * q + (j0 + 1 < rem ? j0 + 1 : rem);
+    const u32 keeps = d + 1 == N ? 0 : d + 1;  // the segment destination d owns
+    const void *src0 = a.buf[(j0 == 0 ? N : j0) - 1];
+    const void *src1 = a.buf[j0];              // owner of segment j0 + 1
+    void *dst = a.buf[d];
+
+    vec16 v[ITERS];
+    u32 how[ITERS];  // 0 nothing, 1 whole vector from src0, 2 whole vector from src1, 3 element by element
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const u64 b = (v0 + (u64)it * kThreads + threadIdx.x) << 4;
+        const u64 x0 = b >> T::kShift, x1 = (b + 16) >> T::kShift;
+        how[it] = 0;
+        if (b >= r1) continue;
+        if (b + 16 > r1 || (x0 < bnd && x1 > bnd))
+            how[it] = 3;
+        else if (x0 >= bnd)
+            how[it] = (j0 + 1 == keeps) ? 0 : 2;
+        else
+            how[it] = (j0 == keeps) ? 0 : 1;
+        if (how[it] == 1) v[it] = VecPacket<T>::load_again(src0, b);
+        if (how[it] == 2) v[it] = VecPacket<T>::load_again(src1, b);
+    }
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const u64 b = (v0 + (u64)it * kThreads + threadIdx.x) << 4;
+        if (how[it] == 1 || how[it] == 2) {
+            VecPacket<T>::store(dst, b, v[it]);
+        } else if (how[it] == 3) {
+            const u64 end = b + 16 < r1 ? b + 16 : r1;
+            for (u64 e = b; e < end; e += sizeof(elem_t)) {
+                const bool second = (e >> T::kShift) >= bnd;
+                if ((second ? j0 + 1 : j0) != keeps)
+                    ElemPacket<T>::store(dst, e, ElemPacket<T>::load(second ? src1 : src0, e));
+            }
+        }
+    }
+}
+
+// nz_gather_bcast (any segment length; used when segments are shorter than a
+// tile): one workgroup reads a tile of a segment once and stores it to all
+// N - 1 destinations.  Same tiling as a ring step.  A pure copy, so T only
+// fixes the element size of the edge path.
 struct GatherArgs {
     RailGeom g;
-    u32 pps[NZ_MAX_RAILS];  // pieces per segment of each rail
-    u32 grp[NZ_MAX_RAILS];  // destinations per workgroup of each rail
     void *buf[NZ_MAX_NODES];
 };
 
 template <class P>
-__device__ __forceinline__ typename P::raw_t gather_load(const NZ_KARG GatherArgs &a, u32 owner, bool once,
-                                                         u64 byte_off)
+__device__ __forceinline__ void gather_at(const NZ_KARG GatherArgs &a, u32 owner, u64 byte_off)
 {
-    return once ? P::load(a.buf[owner], byte_off) : P::load_again(a.buf[owner], byte_off);
-}
-
-template <class P>
-__device__ __forceinline__ void gather_at(const NZ_KARG GatherArgs &a, u32 owner, u32 d0, u32 d1, bool once,
-                                          u64 byte_off)
-{
-    const typename P::raw_t v = gather_load<P>(a, owner, once, byte_off);
-    for (u32 d = d0; d < d1; ++d) P::store(a.buf[d < owner ? d : d + 1], byte_off, v);  // the nodes other than the owner
+    const typename P::raw_t v = P::load(a.buf[owner], byte_off);
+    for (u32 m = 0; m < a.g.n_nodes; ++m)
+        if (m != owner) P::store(a.buf[m], byte_off, v);
 }
 
 template <class T, int ITERS>
@@ -804,49 +867,27 @@ __global__ __launch_bounds__(kThreads) void nz_gather_bcast(const GatherArgs)
 {
     const NZ_KARG GatherArgs &a = kernel_args<GatherArgs>();
     constexpr int TILE = ITERS * kThreads;
-    const u32 N = a.g.n_nodes;
-    u32 rail = 0;
-    while (rail + 1 < a.g.n_rails && blockIdx.x >= a.g.tile0[rail + 1]) ++rail;
-    const u32 grp = a.grp[rail], n_groups = (N - 1 + grp - 1) / grp;
-    u32 rest = blockIdx.x - a.g.tile0[rail];
-    const u32 tile = rest % a.g.tps[rail];
-    rest /= a.g.tps[rail];
-    const u32 group = rest % n_groups;
-    rest /= n_groups;
-    const u32 piece = rest % a.pps[rail], seg = rest / a.pps[rail];
-    const SegTile t =
-        segment_tile<TILE>(a.g, rail, seg, tile, T::kShift, (u64)piece * a.g.win_len, a.g.win_len);
+    u32 rail, seg, tile;
+    decode_block(a.g, blockIdx.x, rail, seg, tile);
+    const SegTile t = segment_tile<TILE>(a.g, rail, seg, tile, T::kShift);
     if (t.vec_lo >= t.vec_hi) return;
-    const u32 owner = (seg == 0 ? N : seg) - 1;
-    const u32 d0 = group * grp, d1 = d0 + grp < N - 1 ? d0 + grp : N - 1;
-    const bool once = n_groups == 1;
+    const u32 owner = (seg == 0 ? a.g.n_nodes : seg) - 1;
 
     const u64 full_lo = (t.b0 + 15) >> 4, full_hi = t.b1 >> 4;
     const u64 lo = t.vec_lo > full_lo ? t.vec_lo : full_lo;
     const u64 hi = t.vec_hi < full_hi ? t.vec_hi : full_hi;
-    // All of the thread's loads first, then the stores, destination by destination.
-    vec16 v[ITERS];
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         const u64 vec = t.tile_base + (u64)it * kThreads + threadIdx.x;
-        if (vec >= lo && vec < hi) v[it] = gather_load<VecPacket<T>>(a, owner, once, vec << 4);
-    }
-    for (u32 d = d0; d < d1; ++d) {
-        void *dst = a.buf[d < owner ? d : d + 1];  // the nodes other than the owner
-#pragma unroll
-        for (int it = 0; it < ITERS; ++it) {
-            const u64 vec = t.tile_base + (u64)it * kThreads + threadIdx.x;
-            if (vec >= lo && vec < hi) VecPacket<T>::store(dst, vec << 4, v[it]);
-        }
+        if (vec >= lo && vec < hi) gather_at<VecPacket<T>>(a, owner, vec << 4);
     }
     const u64 head_end = (full_lo << 4) < t.b1 ? (full_lo << 4) : t.b1;
     u64 tail_beg = full_hi << 4;
     if (tail_beg < head_end) tail_beg = head_end;
     const u64 eoff = (u64)threadIdx.x << T::kShift;
-    if (t.vec_lo == (t.b0 >> 4) && t.b0 + eoff < head_end)
-        gather_at<ElemPacket<T>>(a, owner, d0, d1, once, t.b0 + eoff);
+    if (t.vec_lo == (t.b0 >> 4) && t.b0 + eoff < head_end) gather_at<ElemPacket<T>>(a, owner, t.b0 + eoff);
     if (t.vec_hi == ((t.b1 + 15) >> 4) && tail_beg + eoff < t.b1)
-        gather_at<ElemPacket<T>>(a, owner, d0, d1, once, tail_beg + eoff);
+        gather_at<ElemPacket<T>>(a, owner, tail_beg + eoff);
 }
 
 // ---------------------------------------------------------------------------

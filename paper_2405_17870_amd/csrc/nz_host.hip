@@ -138,6 +138,14 @@ constexpr u64 kStageMinBytes = NZ_STAGE_MIN_BYTES;
 constexpr u64 kStageMinOutputBytes = NZ_STAGE_MIN_OUTPUT_BYTES;
 u64 round_up(u64 x, u64 m) { return (x + m - 1) / m * m; }
 
+// A span of `span` bytes is cut into equal pieces of at most kStagePieceBytes,
+// each a whole number of 4 KB tiles.
+u64 stage_piece_bytes(u64 span)
+{
+    const u64 n_pieces = (span + kStagePieceBytes - 1) / kStagePieceBytes;
+    return round_up((span + n_pieces - 1) / n_pieces, (u64)kThreads * 16);
+}
+
 template <class T>
 nz_status launch_stage(StageArgs &a, hipStream_t st)
 {
@@ -177,8 +185,7 @@ nz_status launch_staged(StageArgs &a, const u64 *rail_off, u32 n_rails, u32 rail
         const u64 lo = rail_off[k] << elem_shift, hi = rail_off[end] << elem_shift;
         k = end;
         if (hi == lo) continue;
-        const u64 n_pieces = (hi - lo + kStagePieceBytes - 1) / kStagePieceBytes;
-        const u64 piece = round_up((hi - lo + n_pieces - 1) / n_pieces, (u64)kThreads * 16);
+        const u64 piece = stage_piece_bytes(hi - lo);
         for (u64 p = lo; p < hi; p += piece) {
             a.a_lo = p;
             a.a_hi = std::min(hi, p + piece);
@@ -201,7 +208,7 @@ nz_status launch_staged(StageArgs &a, const u64 *rail_off, u32 n_rails, u32 rail
 #endif
 constexpr int kRingIters = NZ_RING_ITERS;
 #ifndef NZ_GATHER_ITERS
-#define NZ_GATHER_ITERS 2
+#define NZ_GATHER_ITERS 4
 #endif
 constexpr int kGatherIters = NZ_GATHER_ITERS;
 
@@ -301,47 +308,46 @@ nz_status launch_gather(const GatherArgs &a, u32 blocks, hipStream_t st)
     return e == hipSuccess ? NZ_OK : hip_failed(e, "direct allgather launch");
 }
 
-// Segment (piece) size from which the direct allgather serves one destination
-// buffer at a time.
-#ifndef NZ_GATHER_ONE_BY_ONE_BYTES
-#define NZ_GATHER_ONE_BY_ONE_BYTES (1ull << 20)
-#endif
-constexpr u64 kGatherOneByOneBytes = NZ_GATHER_ONE_BY_ONE_BYTES;
+template <class T>
+nz_status launch_gather_range(const GatherRangeArgs &a, u32 blocks, hipStream_t st)
+{
+    const hipError_t e = launch(nz_gather_range<T, kGatherIters>, blocks, a, st);
+    return e == hipSuccess ? NZ_OK : hip_failed(e, "direct allgather launch");
+}
 
-// Geometry of the direct allgather: per rail N segments x pieces x (N - 1)
-// destinations x tiles.  Returns the number of workgroups (as build_geometry).
-u64 build_gather_geometry(GatherArgs &a, const u64 *rail_off, u32 n_rails, u32 n_nodes, u32 elem_shift,
-                          u32 tile_vecs, u32 rail_mask)
+// Geometry of the direct allgather one destination at a time: per rail pieces
+// x N destinations x tiles.  Returns the number of workgroups (as
+// build_geometry), or kNotForRanges if some rail's segments are shorter than a
+// tile, which that kernel does not handle.
+constexpr u64 kNotForRanges = UINT64_MAX - 1;
+
+u64 build_gather_ranges(GatherRangeArgs &a, const u64 *rail_off, u32 n_rails, u32 n_nodes, u32 elem_shift,
+                        u32 tile_vecs, u32 rail_mask)
 {
     std::memset(&a.g, 0, sizeof a.g);
     RailGeom &g = a.g;
     g.n_rails = n_rails;
     g.n_nodes = n_nodes;
-    g.win_off = 0;
-    g.win_len = kStagePieceBytes >> elem_shift;
+    const u64 tile_bytes = (u64)tile_vecs * 16;
     u64 total = 0;
     for (u32 k = 0; k < n_rails; ++k) {
+        // A rail left out of this launch keeps its place but gets no workgroup.
         const u64 len = (rail_mask >> k & 1u) ? rail_off[k + 1] - rail_off[k] : 0;
         g.off[k] = rail_off[k];
-        g.q[k] = len / n_nodes;
-        g.rem[k] = (u32)(len % n_nodes);
+        g.q[k] = (rail_off[k + 1] - rail_off[k]) / n_nodes;
+        g.rem[k] = (u32)((rail_off[k + 1] - rail_off[k]) % n_nodes);
         g.tile0[k] = (u32)total;
-        const u64 longest = g.q[k] + (g.rem[k] ? 1 : 0);
-        a.pps[k] = 1;
-        a.grp[k] = n_nodes - 1;
-        g.tps[k] = 0;
-        if (longest == 0) continue;
-        const u64 pieces = (longest + g.win_len - 1) / g.win_len;
-        // Pieces start anywhere: bound the tiles a piece can touch; a multiple of 8.
-        const u64 vecs = ((std::min<u64>(longest, g.win_len) << elem_shift) + 15) / 16 + 1;
-        const u64 tiles = round_up((vecs + tile_vecs - 1) / tile_vecs + 1, 8);
-        if (pieces > 0xffffffffull || tiles > 0xffffffffull) return 0;
-        a.pps[k] = (u32)pieces;
-        g.tps[k] = (u32)tiles;
-        // One destination at a time pays once a piece outlasts the workgroups in flight.
-        a.grp[k] = ((std::min<u64>(longest, g.win_len) << elem_shift) >= kGatherOneByOneBytes) ? 1 : n_nodes - 1;
-        const u64 groups = (n_nodes - 1 + a.grp[k] - 1) / a.grp[k];
-        total += (u64)n_nodes * pieces * groups * tiles;
+        a.pieces[k] = 0;
+        g.tps[k] = 1;
+        if (len == 0) continue;
+        if ((g.q[k] << elem_shift) < tile_bytes) return kNotForRanges;
+        const u64 bytes = len << elem_shift;
+        const u64 tps = round_up((stage_piece_bytes(bytes) + tile_bytes - 1) / tile_bytes, 8);
+        const u64 pieces = (bytes + tps * tile_bytes - 1) / (tps * tile_bytes);
+        if (pieces > 0xffffffffull) return 0;
+        a.pieces[k] = (u32)pieces;
+        g.tps[k] = (u32)tps;
+        total += pieces * n_nodes * tps;
         if (total > 0x7fffffffull) return 0;
     }
     g.off[n_rails] = rail_off[n_rails];
@@ -475,9 +481,22 @@ nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t
 
     if (mode == NZ_FUSED && what == kAllgather) {
         if (n_nodes == 1) return NZ_OK;
+        {
+            // One destination buffer at a time, if every rail's segments are at least a tile long.
+            GatherRangeArgs a;
+            const u64 blocks = build_gather_ranges(a, rail_off, n_rails, n_nodes, shift,
+                                                   (u32)kGatherIters * kThreads, rail_mask);
+            if (blocks == 0) return NZ_ERR_UNSUPPORTED;
+            if (blocks == kNothingToDo) return NZ_OK;
+            if (blocks != kNotForRanges) {
+                for (u32 i = 0; i < n_nodes; ++i) a.buf[i] = out_bufs[i];
+                return eb == 4 ? launch_gather_range<TI32>(a, (u32)blocks, st)
+                               : launch_gather_range<TBF16>(a, (u32)blocks, st);
+            }
+        }
         GatherArgs a;
-        const u64 blocks = build_gather_geometry(a, rail_off, n_rails, n_nodes, shift,
-                                                 (u32)kGatherIters * kThreads, rail_mask);
+        const u64 blocks =
+            build_geometry(a.g, rail_off, n_rails, n_nodes, shift, (u32)kGatherIters * kThreads, rail_mask);
         if (blocks == 0) return NZ_ERR_UNSUPPORTED;
         if (blocks == kNothingToDo) return NZ_OK;
         for (u32 i = 0; i < n_nodes; ++i) a.buf[i] = out_bufs[i];
@@ -624,8 +643,10 @@ nz_status nz_allreduce_launches(uint32_t n_nodes, uint64_t n_elems, const uint32
         *launches = 1;
         return NZ_OK;
     }
-    // The staged pipeline: all rails take part, so the message is one span.
-    *launches = (bytes + kStagePieceBytes - 1) / kStagePieceBytes + 1;
+    // The staged pipeline: all rails take part, so the message is one span; one
+    // launch per piece and one more that spreads the last piece.
+    const u64 piece = stage_piece_bytes(bytes);
+    *launches = (bytes + piece - 1) / piece + 1;
     return NZ_OK;
 }
 
