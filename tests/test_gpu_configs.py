@@ -109,6 +109,13 @@ def test_c5_128_nodes_full_compare(orc):
     outs = _run(w, "fused", ins)
     assert _all_equal(outs)
     gu.check_fused_against_oracle(orc, "f32", inputs.to_host_storage(outs[0]), host, "c5 fused")
+    _say("c5: fused reduce-scatter, then the direct allgather (segments of 21 KB to 210 KB)")
+    parts = [torch.full_like(t, float("nan")) for t in ins]
+    nz.nz_reduce_scatter_sim(ins, w.n_elems, w.ratios, w.dtype, "fused", parts)
+    nz.nz_allgather_sim(parts, w.n_elems, w.ratios, w.dtype, "fused")
+    torch.cuda.synchronize()
+    assert all(torch.equal(p, outs[0]) for p in parts)
+    del parts
     _say("c5: ring-stepwise")
     outs = _run(w, "ring-stepwise", ins)
     assert _all_equal(outs)

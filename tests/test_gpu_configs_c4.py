@@ -64,7 +64,7 @@ def c4():
 def test_c4_fused_whole_range(orc, c4):
     """Every one of the 335 M sums against the oracle, in element-range chunks (32 slices of
     16 MB at a time through pinned host memory), plus bitwise equality of all 32 outputs."""
-    w, arena, ins, outs = c4
+    w, arena, ins, outs = c4[:4]
     N, n = w.n_nodes, w.n_elems
     for t in outs:
         t.zero_()
@@ -114,7 +114,7 @@ def test_c4_ring_stepwise_windows(orc, c4):
     """The 62 ring steps at full size (670 MB per step: the streaming step kernels), checked
     bit for bit on sampled windows: the oracle's literal ring runs on the 32 extracted windows
     under the segment table clipped to the window and re-based to its start."""
-    w, arena, ins, outs = c4
+    w, arena, ins, outs = c4[:4]
     N, n = w.n_nodes, w.n_elems
     for t in outs:
         t.zero_()
@@ -133,11 +133,107 @@ def test_c4_ring_stepwise_windows(orc, c4):
         assert all(np.array_equal(want[0], x) for x in want[1:])
 
 
+def _second_outputs(c4):
+    """A second set of 32 result buffers, made on first use and kept for the rest of the file."""
+    w, arena, ins, outs = c4[:4]
+    if len(c4) == 4:
+        c4.append(arena.alloc_striped(w.n_nodes, w.n_elems, torch.bfloat16, start=1) if arena is not None
+                  else [torch.empty_like(t) for t in ins])
+    return c4[4]
+
+
+def _canary(bufs):
+    for t in bufs:
+        t.view(torch.uint8).fill_(0xC3)
+
+
+@pytest.mark.parametrize("mode", ["fused", "ring-stepwise"])
+def test_c4_phases_at_full_size(orc, c4, mode):
+    """Reduce-scatter alone and allgather alone at full size (the direct allgather works through
+    each rail in many cache-sized pieces here; small shapes have one).  The allreduce of the
+    same mode, checked against the oracle on sampled windows, is the reference: after the
+    reduce-scatter node r holds exactly its own segments of it and nothing else was written;
+    after the allgather every node holds all of it."""
+    w, arena, ins, outs = c4[:4]
+    N, n = w.n_nodes, w.n_elems
+    second = _second_outputs(c4)
+    _say(f"c4 phases: {mode} allreduce as the reference")
+    nz.nz_allreduce_sim(ins, n, w.ratios, w.dtype, mode, outs)
+    torch.cuda.synchronize()
+    assert _all_equal(outs)
+    seg, windows = _points_c4(w, orc, np.random.default_rng(11))
+    for lo, hi in windows[:8:2] + windows[-2:]:
+        host = [inputs.to_host_storage(t[lo:hi]) for t in ins]
+        got = inputs.to_host_storage(outs[N - 1][lo:hi])
+        if mode == "fused":
+            gu.check_fused_against_oracle(orc, "bf16", got, host, f"c4 [{lo}:{hi}]")
+        else:
+            local = (np.clip(seg.astype(np.int64), lo, hi) - lo).astype(np.uint64)
+            want, _ = orc.ring_allreduce(orc.BF16, host, local)
+            gu.assert_same_bits(got, want[N - 1], "bf16", f"c4 ring [{lo}:{hi}]")
+    ref = outs[0]
+    _say(f"c4 phases: {mode} reduce-scatter")
+    _canary(second)
+    nz.nz_reduce_scatter_sim(ins, n, w.ratios, w.dtype, mode, second)
+    torch.cuda.synchronize()
+    if mode == "fused":
+        for r in range(N):
+            j = (r + 1) % N
+            edge = 0
+            for k in range(seg.shape[0]):
+                lo, hi = int(seg[k, j]), int(seg[k, j + 1])
+                assert torch.equal(second[r][lo:hi], ref[lo:hi]), (r, k)
+                assert bool((second[r][edge:lo].view(torch.uint8) == 0xC3).all()), (r, k)
+                edge = hi
+            assert bool((second[r][edge:].view(torch.uint8) == 0xC3).all()), r
+    else:
+        # the ring's reduce-scatter leaves partial sums in the other segments; the owned ones
+        # are final
+        for r in range(N):
+            j = (r + 1) % N
+            for k in range(seg.shape[0]):
+                lo, hi = int(seg[k, j]), int(seg[k, j + 1])
+                assert torch.equal(second[r][lo:hi], ref[lo:hi]), (r, k)
+    _say(f"c4 phases: {mode} allgather")
+    nz.nz_allgather_sim(second, n, w.ratios, w.dtype, mode)
+    torch.cuda.synchronize()
+    for r in range(N):
+        assert torch.equal(second[r], ref), r
+
+
+def test_c4_chunked_and_failover_at_full_size(orc, c4):
+    """Ring_Chunked (pieces of 1 Mi and of 256 Ki elements, the benchmark's settings) gives the
+    stepwise ring's bits, the failover allreduce the fused sums, whichever rail fails; the two
+    references are checked against the oracle by the tests above."""
+    w, arena, ins, outs = c4[:4]
+    N, n = w.n_nodes, w.n_elems
+    second = _second_outputs(c4)
+    nz.nz_allreduce_sim(ins, n, w.ratios, w.dtype, "ring-stepwise", outs)
+    for chunk in (1 << 20, 1 << 18):
+        _say(f"c4: Ring_Chunked, pieces of {chunk} elements")
+        _canary(second)
+        nz.nz_allreduce_sim_chunked(ins, n, w.ratios, w.dtype, chunk, second)
+        torch.cuda.synchronize()
+        for r in range(N):
+            assert torch.equal(second[r], outs[r]), (chunk, r)
+    nz.nz_allreduce_sim(ins, n, w.ratios, w.dtype, "fused", outs)
+    b = orc.rail_partition(n, w.ratios, 2)
+    for failed in range(len(w.ratios)):
+        _say(f"c4: failover, rail {failed} fails")
+        _canary(second)
+        took = nz.nz_allreduce_sim_failover(ins, n, w.ratios, w.dtype, "fused", second, failed)
+        torch.cuda.synchronize()
+        alive = [k != failed for k in range(len(w.ratios))]
+        assert took == orc.failover_target(b, alive)
+        for r in range(N):
+            assert torch.equal(second[r], outs[0]), (failed, r)
+
+
 def test_c4_pack_route_unpack(orc, c4):
     """Whole-rail pack and unpack at full size: packed bytes and unpacked bytes of sampled
     nodes against the oracle; the route pack -> fused allreduce of the send buffers -> unpack
     gives bitwise the sums of the direct call."""
-    w, arena, ins, outs = c4
+    w, arena, ins, outs = c4[:4]
     N, n = w.n_nodes, w.n_elems
     nz.nz_allreduce_sim(ins, n, w.ratios, w.dtype, "fused", outs)
     b = nz.nz_rail_partition(n, 2, w.ratios)
