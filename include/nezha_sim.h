@@ -181,11 +181,13 @@ nz_status nz_allreduce_launches(uint32_t n_nodes, uint64_t n_elems, const uint32
  * pairwise distinct, non-overlapping).  On entry node r's buffer holds valid
  * data in segment (r + 1) mod N of every rail; on exit every buffer holds
  * every segment.  NZ_RING_STEPWISE: N - 1 launches (step s copies segment
- * (r + 1 - s) mod N from node r to node r + 1); NZ_FUSED: one launch, each
- * segment read from its owner and stored to the other N - 1 buffers -- one
- * destination buffer after the other over pieces of at most 24 MiB of a rail
- * (all passes but the first read the piece from the L2 caches), or, when
- * segments are shorter than 16 KiB, all destinations from one read.
+ * (r + 1 - s) mod N from node r to node r + 1); NZ_FUSED: each segment read
+ * from its owner and stored to the other N - 1 buffers, in one launch for
+ * the rails whose segments are at least 16 KiB long -- one destination buffer
+ * after the other over pieces of at most 24 MiB of a rail (all passes but the
+ * first read the piece from the L2 caches) -- and one more launch, if there
+ * are such rails, for those with shorter segments (all destinations from one
+ * read).
  * dtype only fixes the element size.
  *
  * nz_reduce_scatter_sim followed by nz_allgather_sim on its outputs gives

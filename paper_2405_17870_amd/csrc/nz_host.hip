@@ -316,13 +316,11 @@ nz_status launch_gather_range(const GatherRangeArgs &a, u32 blocks, hipStream_t 
 }
 
 // Geometry of the direct allgather one destination at a time: per rail pieces
-// x N destinations x tiles.  Returns the number of workgroups (as
-// build_geometry), or kNotForRanges if some rail's segments are shorter than a
-// tile, which that kernel does not handle.
-constexpr u64 kNotForRanges = UINT64_MAX - 1;
-
+// x N destinations x tiles.  Rails whose segments are shorter than a tile are
+// not for this kernel: they get no workgroup here and their bits are returned
+// in *short_rails.  Returns the number of workgroups (as build_geometry).
 u64 build_gather_ranges(GatherRangeArgs &a, const u64 *rail_off, u32 n_rails, u32 n_nodes, u32 elem_shift,
-                        u32 tile_vecs, u32 rail_mask)
+                        u32 tile_vecs, u32 rail_mask, u32 *short_rails)
 {
     std::memset(&a.g, 0, sizeof a.g);
     RailGeom &g = a.g;
@@ -330,6 +328,7 @@ u64 build_gather_ranges(GatherRangeArgs &a, const u64 *rail_off, u32 n_rails, u3
     g.n_nodes = n_nodes;
     const u64 tile_bytes = (u64)tile_vecs * 16;
     u64 total = 0;
+    *short_rails = 0;
     for (u32 k = 0; k < n_rails; ++k) {
         // A rail left out of this launch keeps its place but gets no workgroup.
         const u64 len = (rail_mask >> k & 1u) ? rail_off[k + 1] - rail_off[k] : 0;
@@ -340,7 +339,10 @@ u64 build_gather_ranges(GatherRangeArgs &a, const u64 *rail_off, u32 n_rails, u3
         a.pieces[k] = 0;
         g.tps[k] = 1;
         if (len == 0) continue;
-        if ((g.q[k] << elem_shift) < tile_bytes) return kNotForRanges;
+        if ((g.q[k] << elem_shift) < tile_bytes) {
+            *short_rails |= 1u << k;
+            continue;
+        }
         const u64 bytes = len << elem_shift;
         const u64 tps = round_up((stage_piece_bytes(bytes) + tile_bytes - 1) / tile_bytes, 8);
         const u64 pieces = (bytes + tps * tile_bytes - 1) / (tps * tile_bytes);
@@ -481,26 +483,33 @@ nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t
 
     if (mode == NZ_FUSED && what == kAllgather) {
         if (n_nodes == 1) return NZ_OK;
-        {
-            // One destination buffer at a time, if every rail's segments are at least a tile long.
-            GatherRangeArgs a;
-            const u64 blocks = build_gather_ranges(a, rail_off, n_rails, n_nodes, shift,
-                                                   (u32)kGatherIters * kThreads, rail_mask);
-            if (blocks == 0) return NZ_ERR_UNSUPPORTED;
-            if (blocks == kNothingToDo) return NZ_OK;
-            if (blocks != kNotForRanges) {
-                for (u32 i = 0; i < n_nodes; ++i) a.buf[i] = out_bufs[i];
-                return eb == 4 ? launch_gather_range<TI32>(a, (u32)blocks, st)
-                               : launch_gather_range<TBF16>(a, (u32)blocks, st);
-            }
+        // One destination buffer at a time for the rails whose segments are at least a tile
+        // long, all destinations at once for the others.  Both geometries are built before
+        // anything is launched, so a refusal launches nothing.
+        GatherRangeArgs ra;
+        GatherArgs ga;
+        u32 short_rails = 0;
+        const u32 tile_vecs = (u32)kGatherIters * kThreads;
+        const u64 range_blocks =
+            build_gather_ranges(ra, rail_off, n_rails, n_nodes, shift, tile_vecs, rail_mask, &short_rails);
+        if (range_blocks == 0) return NZ_ERR_UNSUPPORTED;
+        u64 short_blocks = kNothingToDo;
+        if (short_rails != 0) {
+            short_blocks = build_geometry(ga.g, rail_off, n_rails, n_nodes, shift, tile_vecs, short_rails);
+            if (short_blocks == 0) return NZ_ERR_UNSUPPORTED;
         }
-        GatherArgs a;
-        const u64 blocks =
-            build_geometry(a.g, rail_off, n_rails, n_nodes, shift, (u32)kGatherIters * kThreads, rail_mask);
-        if (blocks == 0) return NZ_ERR_UNSUPPORTED;
-        if (blocks == kNothingToDo) return NZ_OK;
-        for (u32 i = 0; i < n_nodes; ++i) a.buf[i] = out_bufs[i];
-        return eb == 4 ? launch_gather<TI32>(a, (u32)blocks, st) : launch_gather<TBF16>(a, (u32)blocks, st);
+        if (range_blocks != kNothingToDo) {
+            for (u32 i = 0; i < n_nodes; ++i) ra.buf[i] = out_bufs[i];
+            const nz_status s = eb == 4 ? launch_gather_range<TI32>(ra, (u32)range_blocks, st)
+                                        : launch_gather_range<TBF16>(ra, (u32)range_blocks, st);
+            if (s != NZ_OK) return s;
+        }
+        if (short_blocks != kNothingToDo) {
+            for (u32 i = 0; i < n_nodes; ++i) ga.buf[i] = out_bufs[i];
+            return eb == 4 ? launch_gather<TI32>(ga, (u32)short_blocks, st)
+                           : launch_gather<TBF16>(ga, (u32)short_blocks, st);
+        }
+        return NZ_OK;
     }
 
     if (mode == NZ_FUSED) {
