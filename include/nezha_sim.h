@@ -120,10 +120,10 @@ nz_status nz_segment_map(const uint64_t *rail_off, uint32_t n_rails, uint32_t n_
  *   NZ_FUSED: every element is read once from all nodes, summed in fp32
  *     registers (int32: wrapping integer add) in a fixed blocked pairwise
  *     order that depends on n_nodes only, rounded once to `dtype` (nearest
- *     even) and written once to every distinct output buffer.  With a
- *     single distinct output buffer, or while the outputs together take
- *     less than 128 MiB, this is one launch whose unit of work is a tile
- *     of a segment.  Larger jobs run as a short pipeline of launches over
+ *     even) and written once to every distinct output buffer.  With fewer
+ *     than seven distinct output buffers, or while the outputs together
+ *     take less than 128 MiB, this is one launch whose unit of work is a
+ *     tile of a segment.  Larger jobs run as a short pipeline of launches over
  *     pieces of at most 24 MiB of the participating rails: launch c sums
  *     piece c into one of the output buffers (the one farthest from the
  *     inputs) and copies piece c - 1 from there (re-read through the L2

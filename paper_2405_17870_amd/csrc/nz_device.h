@@ -359,28 +359,45 @@ __device__ __forceinline__ void block_sum8(NodeTable in, u32 m0, u64 byte_off,
                ((P::lane(r[4], l) + P::lane(r[5], l)) + (P::lane(r[6], l) + P::lane(r[7], l)));
 }
 
-// Sum of the last, partial block (1 <= nb <= 7 nodes): the same tree with the
-// missing leaves left out.
-template <class T, class P, bool CACHED>
-__device__ __forceinline__ void block_sum_tail(NodeTable in, u32 m0, u32 nb, u64 byte_off,
+// Sum of a partial block of NB nodes (1 <= NB <= 7): the same tree with the
+// missing leaves left out, and no load for them either.
+template <class T, class P, bool CACHED, int NB>
+__device__ __forceinline__ void block_sum_part(NodeTable in, u32 m0, u64 byte_off,
                                                typename T::acc_t (&s)[P::kLanes])
 {
     typedef typename T::acc_t acc_t;
     typename P::raw_t r[7];
 #pragma unroll
     for (int i = 0; i < 7; ++i) {
-        const void *src = in[(u32)i < nb ? m0 + i : m0];
-        r[i] = CACHED ? P::load_again(src, byte_off) : P::load(src, byte_off);
+        if (i < NB) r[i] = CACHED ? P::load_again(in[m0 + i], byte_off) : P::load(in[m0 + i], byte_off);
     }
 #pragma unroll
     for (int l = 0; l < P::kLanes; ++l) {
-        const acc_t p0 = nb > 1 ? P::lane(r[0], l) + P::lane(r[1], l) : P::lane(r[0], l);
-        const acc_t p1 = nb > 3 ? P::lane(r[2], l) + P::lane(r[3], l) : P::lane(r[2], l);
-        const acc_t p2 = nb > 5 ? P::lane(r[4], l) + P::lane(r[5], l) : P::lane(r[4], l);
-        const acc_t p3 = P::lane(r[6], l);
-        const acc_t lo = nb > 2 ? p0 + p1 : p0;
-        const acc_t hi = nb > 6 ? p2 + p3 : p2;
-        s[l] = nb > 4 ? lo + hi : lo;
+        // r[i] with i >= NB is never read: each use below is guarded by the same comparison
+        const acc_t p0 = NB > 1 ? P::lane(r[0], l) + P::lane(r[1 < NB ? 1 : 0], l) : P::lane(r[0], l);
+        const acc_t p1 = NB > 3 ? P::lane(r[2], l) + P::lane(r[3 < NB ? 3 : 0], l) : P::lane(r[2 < NB ? 2 : 0], l);
+        const acc_t p2 = NB > 5 ? P::lane(r[4], l) + P::lane(r[5 < NB ? 5 : 0], l) : P::lane(r[4 < NB ? 4 : 0], l);
+        const acc_t p3 = P::lane(r[6 < NB ? 6 : 0], l);
+        const acc_t lo = NB > 2 ? p0 + p1 : p0;
+        const acc_t hi = NB > 6 ? p2 + p3 : p2;
+        s[l] = NB > 4 ? lo + hi : lo;
+    }
+}
+
+// The last, partial block of a sum (1 <= nb <= 7 nodes, the same for every
+// thread of the launch).
+template <class T, class P, bool CACHED>
+__device__ __forceinline__ void block_sum_tail(NodeTable in, u32 m0, u32 nb, u64 byte_off,
+                                               typename T::acc_t (&s)[P::kLanes])
+{
+    switch (nb) {
+    case 1: block_sum_part<T, P, CACHED, 1>(in, m0, byte_off, s); break;
+    case 2: block_sum_part<T, P, CACHED, 2>(in, m0, byte_off, s); break;
+    case 3: block_sum_part<T, P, CACHED, 3>(in, m0, byte_off, s); break;
+    case 4: block_sum_part<T, P, CACHED, 4>(in, m0, byte_off, s); break;
+    case 5: block_sum_part<T, P, CACHED, 5>(in, m0, byte_off, s); break;
+    case 6: block_sum_part<T, P, CACHED, 6>(in, m0, byte_off, s); break;
+    default: block_sum_part<T, P, CACHED, 7>(in, m0, byte_off, s); break;
     }
 }
 
@@ -496,14 +513,13 @@ __device__ __forceinline__ typename P::raw_t reduce_at(NodeTable in, u32 N, u64 
     return P::narrow(res);
 }
 
-// Reduce one packet position and store it to out[out_begin .. out_end).  The
-// stores start at a buffer that depends on the workgroup, so that workgroups
-// running at the same time write to different buffers.
-template <class T, class P, int CLASS, bool CACHED>
-__device__ __forceinline__ void reduce_bcast_at(const NZ_KARG FusedArgs &a, u64 byte_off, u32 out_begin,
-                                                u32 out_end)
+// Store one reduced packet to out[out_begin .. out_end).  The stores start at
+// a buffer that depends on the workgroup, so that workgroups running at the
+// same time write to different buffers.
+template <class P, bool CACHED>
+__device__ __forceinline__ void bcast_at(const NZ_KARG FusedArgs &a, u64 byte_off, u32 out_begin, u32 out_end,
+                                         typename P::raw_t packed)
 {
-    const typename P::raw_t packed = reduce_at<T, P, CLASS, CACHED>(a.in, a.g.n_nodes, byte_off);
     const u32 K = out_end - out_begin;
     u32 o = out_begin + blockIdx.x % K;
     for (u32 i = 0; i < K; ++i) {
@@ -515,12 +531,25 @@ __device__ __forceinline__ void reduce_bcast_at(const NZ_KARG FusedArgs &a, u64 
     }
 }
 
+template <class T, class P, int CLASS, bool CACHED>
+__device__ __forceinline__ void reduce_bcast_at(const NZ_KARG FusedArgs &a, u64 byte_off, u32 out_begin,
+                                                u32 out_end)
+{
+    bcast_at<P, CACHED>(a, byte_off, out_begin, out_end,
+                        reduce_at<T, P, CLASS, CACHED>(a.in, a.g.n_nodes, byte_off));
+}
+
 // The grid has two kinds of workgroups.  The first g.tile0[n_rails] of them
-// each take one aligned tile of 256 vectors of one segment and handle the
-// vectors that lie wholly inside it.  They are followed by one workgroup per
-// (rail, segment) for the elements that share a 16-byte vector with a
+// each take one aligned tile of VPT x 256 vectors of one segment and handle
+// the vectors that lie wholly inside it.  They are followed by one workgroup
+// per (rail, segment) for the elements that share a 16-byte vector with a
 // neighbouring segment or with the end of the buffer: one thread per element.
-template <class T, int CLASS, bool CACHED>
+// VPT, vectors per thread: with few nodes a thread has few loads of its own
+// to keep in flight, so it takes several vectors and issues the loads of all
+// of them before the first store (used for jobs that run out of the
+// last-level cache, where latency is what bounds them; a job that streams
+// from HBM is no faster for it).
+template <class T, int CLASS, bool CACHED, int VPT>
 __global__ __launch_bounds__(kThreads) void nz_fused_reduce_bcast(const FusedArgs)
 {
     const NZ_KARG FusedArgs &a = kernel_args<FusedArgs>();
@@ -528,14 +557,25 @@ __global__ __launch_bounds__(kThreads) void nz_fused_reduce_bcast(const FusedArg
     if (blockIdx.x < n_tiles) {
         u32 rail, seg, tile;
         decode_block(a.g, blockIdx.x, rail, seg, tile);
-        const SegTile t = segment_tile<kThreads>(a.g, rail, seg, tile, T::kShift);
+        const SegTile t = segment_tile<VPT * kThreads>(a.g, rail, seg, tile, T::kShift);
         const u64 full_lo = (t.b0 + 15) >> 4, full_hi = t.b1 >> 4;
         const u64 lo = t.vec_lo > full_lo ? t.vec_lo : full_lo;
         const u64 hi = t.vec_hi < full_hi ? t.vec_hi : full_hi;
-        const u64 vec = t.tile_base + threadIdx.x;
         const u32 owner = (seg == 0 ? a.g.n_nodes : seg) - 1;
         const u32 o0 = a.owner_only ? owner : 0, o1 = a.owner_only ? owner + 1 : a.n_out;
-        if (vec >= lo && vec < hi) reduce_bcast_at<T, VecPacket<T>, CLASS, CACHED>(a, vec << 4, o0, o1);
+        typename VecPacket<T>::raw_t packed[VPT];
+        bool mine[VPT];
+#pragma unroll
+        for (int it = 0; it < VPT; ++it) {
+            const u64 vec = t.tile_base + (u64)it * kThreads + threadIdx.x;
+            mine[it] = vec >= lo && vec < hi;
+            if (mine[it]) packed[it] = reduce_at<T, VecPacket<T>, CLASS, CACHED>(a.in, a.g.n_nodes, vec << 4);
+        }
+#pragma unroll
+        for (int it = 0; it < VPT; ++it) {
+            const u64 vec = t.tile_base + (u64)it * kThreads + threadIdx.x;
+            if (mine[it]) bcast_at<VecPacket<T>, CACHED>(a, vec << 4, o0, o1, packed[it]);
+        }
         return;
     }
     const u32 e = blockIdx.x - n_tiles;

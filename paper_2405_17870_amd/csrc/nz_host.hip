@@ -108,34 +108,75 @@ u64 build_geometry(RailGeom &g, const u64 *rail_off, u32 n_rails, u32 n_nodes, u
 // inputs in cache and leaves its results there for whoever reads them next.
 constexpr u64 kFusedCachedBytes = 128ull << 20;
 
+// Vectors per thread of the single-launch fused kernel for a job that runs out
+// of the last-level cache: a thread should have about eight loads of its own in
+// flight, which the blocked sum provides from five nodes on.  (A job that
+// streams from HBM gains nothing from more: measured 1 to 3 % slower.)
+#ifndef NZ_FUSED_VPT_UPTO2
+#define NZ_FUSED_VPT_UPTO2 4
+#endif
+#ifndef NZ_FUSED_VPT_UPTO4
+#define NZ_FUSED_VPT_UPTO4 2
+#endif
+#ifndef NZ_FUSED_VPT_MIN_BLOCKS
+#define NZ_FUSED_VPT_MIN_BLOCKS 2048  // eight workgroups per compute unit
+#endif
+// `bytes`: what the launch reduces, per node.  A small job keeps small tiles so
+// that it still spreads over the whole chip.
+u32 fused_vpt(u32 n_nodes, u64 bytes, bool cached)
+{
+    if (!cached) return 1;
+    u32 vpt = n_nodes <= 2 ? NZ_FUSED_VPT_UPTO2 : n_nodes <= 4 ? NZ_FUSED_VPT_UPTO4 : 1;
+    while (vpt > 1 && bytes / ((u64)vpt * kThreads * 16) < NZ_FUSED_VPT_MIN_BLOCKS) vpt >>= 1;
+    return vpt;
+}
+
 template <class T, bool CACHED>
 hipError_t launch_fused_class(const FusedArgs &a, u32 blocks, hipStream_t st)
 {
-    return a.g.n_nodes <= 8    ? launch(nz_fused_reduce_bcast<T, kUpTo8, CACHED>, blocks, a, st)
-           : a.g.n_nodes <= 32 ? launch(nz_fused_reduce_bcast<T, kUpTo32, CACHED>, blocks, a, st)
-                               : launch(nz_fused_reduce_bcast<T, kAnyN, CACHED>, blocks, a, st);
+    return a.g.n_nodes <= 8    ? launch(nz_fused_reduce_bcast<T, kUpTo8, CACHED, 1>, blocks, a, st)
+           : a.g.n_nodes <= 32 ? launch(nz_fused_reduce_bcast<T, kUpTo32, CACHED, 1>, blocks, a, st)
+                               : launch(nz_fused_reduce_bcast<T, kAnyN, CACHED, 1>, blocks, a, st);
 }
 
+// moved_bytes: what the launch reads and writes; vpt: as chosen by fused_vpt
+// for the same job (the geometry in `a` is built for that tile size).
 template <class T>
-nz_status launch_fused(const FusedArgs &a, u32 blocks, hipStream_t st, u64 moved_bytes)
+nz_status launch_fused(const FusedArgs &a, u32 blocks, hipStream_t st, u64 moved_bytes, u32 vpt)
 {
-    const hipError_t e = moved_bytes <= kFusedCachedBytes ? launch_fused_class<T, true>(a, blocks, st)
-                                                          : launch_fused_class<T, false>(a, blocks, st);
+    const bool cached = moved_bytes <= kFusedCachedBytes;
+    const hipError_t e = vpt == 4   ? launch(nz_fused_reduce_bcast<T, kUpTo8, true, 4>, blocks, a, st)
+                         : vpt == 2 ? launch(nz_fused_reduce_bcast<T, kUpTo8, true, 2>, blocks, a, st)
+                         : cached   ? launch_fused_class<T, true>(a, blocks, st)
+                                    : launch_fused_class<T, false>(a, blocks, st);
     return e == hipSuccess ? NZ_OK : hip_failed(e, "fused reduce launch");
 }
 
-// Payload per node from which the fused allreduce with several output buffers
-// is issued as the staged pipeline (see nz_fused_stage) ...
+// The fused allreduce is issued as the staged pipeline (see nz_fused_stage)
+// from this payload per node, ...
 #ifndef NZ_STAGE_MIN_BYTES
 #define NZ_STAGE_MIN_BYTES (1ull << 20)
 #endif
 constexpr u64 kStageMinBytes = NZ_STAGE_MIN_BYTES;
-// ... and the bytes written to all outputs together (measured on plain
-// allocations: 32 outputs win from 4 MB per node, 8 outputs from 16 MB).
+// ... this many bytes written to all outputs together (measured on plain
+// allocations: 32 outputs win from 4 MB per node, 8 outputs from 16 MB) ...
 #ifndef NZ_STAGE_MIN_OUTPUT_BYTES
 #define NZ_STAGE_MIN_OUTPUT_BYTES (128ull << 20)
 #endif
 constexpr u64 kStageMinOutputBytes = NZ_STAGE_MIN_OUTPUT_BYTES;
+// ... and this many distinct outputs: staging costs one more read of the
+// result, 1 / (N + K) of the traffic, which few write streams do not repay
+// (measured: 2 to 4 outputs lose 3 to 20 %, 6 break even, 8 gain 7 %).
+#ifndef NZ_STAGE_MIN_OUTPUTS
+#define NZ_STAGE_MIN_OUTPUTS 7
+#endif
+constexpr u32 kStageMinOutputs = NZ_STAGE_MIN_OUTPUTS;
+bool staged_allreduce(u32 n_out, u64 active_bytes)
+{
+    return n_out >= kStageMinOutputs && active_bytes >= kStageMinBytes &&
+           active_bytes * n_out >= kStageMinOutputBytes;
+}
+
 u64 round_up(u64 x, u64 m) { return (x + m - 1) / m * m; }
 
 // A span of `span` bytes is cut into equal pieces of at most kStagePieceBytes,
@@ -525,8 +566,7 @@ nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t
         u64 active_bytes = 0;
         for (u32 k = 0; k < n_rails; ++k)
             if (rail_mask >> k & 1u) active_bytes += (rail_off[k + 1] - rail_off[k]) << shift;
-        if (what == kAllreduce && a.n_out >= 2 && active_bytes >= kStageMinBytes &&
-            active_bytes * a.n_out >= kStageMinOutputBytes) {
+        if (what == kAllreduce && staged_allreduce(a.n_out, active_bytes)) {
             // Large message, several outputs: the staged pipeline.
             StageArgs sa;
             std::memset(&sa, 0, sizeof sa);
@@ -566,16 +606,17 @@ nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t
             }
             return NZ_ERR_INVALID_ARG;
         }
-        u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, kThreads, rail_mask);
+        const u64 moved = active_bytes * (n_nodes + (a.owner_only ? 1 : a.n_out));
+        const u32 vpt = fused_vpt(n_nodes, active_bytes, moved <= kFusedCachedBytes);
+        u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, vpt * kThreads, rail_mask);
         if (blocks == 0) return NZ_ERR_UNSUPPORTED;
         if (blocks == kNothingToDo) return NZ_OK;
         blocks += (u64)n_rails * n_nodes;  // the workgroups for segment edges
-        const u64 moved = active_bytes * (n_nodes + (a.owner_only ? 1 : a.n_out));
         switch (dtype) {
-        case NZ_F32: return launch_fused<TF32>(a, (u32)blocks, st, moved);
-        case NZ_I32: return launch_fused<TI32>(a, (u32)blocks, st, moved);
-        case NZ_BF16: return launch_fused<TBF16>(a, (u32)blocks, st, moved);
-        case NZ_F16: return launch_fused<TF16>(a, (u32)blocks, st, moved);
+        case NZ_F32: return launch_fused<TF32>(a, (u32)blocks, st, moved, vpt);
+        case NZ_I32: return launch_fused<TI32>(a, (u32)blocks, st, moved, vpt);
+        case NZ_BF16: return launch_fused<TBF16>(a, (u32)blocks, st, moved, vpt);
+        case NZ_F16: return launch_fused<TF16>(a, (u32)blocks, st, moved, vpt);
         }
         return NZ_ERR_INVALID_ARG;
     }
@@ -648,7 +689,7 @@ nz_status nz_allreduce_launches(uint32_t n_nodes, uint64_t n_elems, const uint32
         return NZ_OK;
     }
     const u64 bytes = n_elems * eb;
-    if (n_distinct_outputs < 2 || bytes < kStageMinBytes || bytes * n_distinct_outputs < kStageMinOutputBytes) {
+    if (!staged_allreduce(n_distinct_outputs, bytes)) {
         *launches = 1;
         return NZ_OK;
     }

@@ -1,11 +1,12 @@
-"""The staged form of the fused allreduce (a pipeline of launches for jobs whose outputs together
-take 128 MiB or more), at the smallest sizes that select it: ragged ends, every element type,
-node counts of all three kernel classes, zero-weight rails, in place, repeated and cross-aliased
-outputs, a failed rail in the middle (two separate spans of rails).
+"""The fused allreduce of large messages: the staged form (a pipeline of launches for jobs with
+seven or more distinct outputs that together take 128 MiB or more) at the smallest sizes that
+select it, and the single-launch form at those sizes for fewer nodes, where a thread works on
+several vectors at once: ragged ends, every element type, node counts of all three kernel
+classes, zero-weight rails, in place, repeated and cross-aliased outputs, a failed rail in the
+middle (two separate spans of rails).
 
 Each result is compared with the CPU oracle, and bitwise with the same call made with ONE shared
-output buffer, which the library runs as a single launch of the other fused kernel: the two
-forms promise the same bits."""
+output buffer, which the library runs as a single launch: all forms promise the same bits."""
 import numpy as np
 import pytest
 import torch
@@ -26,20 +27,23 @@ def _elems_for(N, e, extra):
 
 
 CASES = [
-    # (N, dtype, ratios, ragged extra elements)
-    (2, "f32", (100, 40), 3), (3, "bf16", (3, 1, 2), 5), (8, "f16", (100, 100, 40), 1),
+    # (N, dtype, ratios, ragged extra elements); up to 6 nodes: one launch, 4 or 2 vectors per thread
+    (2, "f32", (100, 40), 3), (3, "bf16", (3, 1, 2), 5), (4, "f16", (1,), 9), (2, "bf16", (0, 3, 1), 1),
+    (4, "i32", (100, 40), 2), (6, "f32", (100, 100, 40), 3),
+    (7, "f32", (100, 40), 3), (8, "bf16", (3, 1, 2), 5), (8, "f16", (100, 100, 40), 1),
     (9, "i32", (7, 0, 3), 2), (32, "bf16", (100, 25), 7), (33, "f32", (1,), 1),
     (128, "f32", (100, 100, 40, 10), 3), (17, "bf16", (0, 5, 0, 2), 6),
 ]
 
 
 @pytest.mark.parametrize("N,dtype,ratios,extra", CASES)
-def test_staged_matches_oracle_and_single_launch(orc, N, dtype, ratios, extra):
+def test_large_fused_matches_oracle_and_single_output_launch(orc, N, dtype, ratios, extra):
     e = inputs.ELEM_BYTES[dtype]
     n = _elems_for(N, e, extra)
-    assert nz.nz_allreduce_launches(N, n, ratios, dtype, "fused", N) > 1       # the pipeline is what runs
+    staged = nz.nz_allreduce_launches(N, n, ratios, dtype, "fused", N) > 1
+    assert staged == (N >= 7)                                                  # the pipeline runs from 7 outputs on
     assert nz.nz_allreduce_launches(N, n, ratios, dtype, "fused", 1) == 1
-    print(f"staged N={N} {dtype} ratios={ratios} n={n}", flush=True)
+    print(f"large fused N={N} {dtype} ratios={ratios} n={n} staged={staged}", flush=True)
     ins = [inputs.node_buffer(dtype, n, 500 + N, i, device=gu.DEV, std=1e-2) for i in range(N)]
     if dtype != "i32":                       # special values at the ragged end and at a piece boundary
         for pos in (n - 1, n - 2, 24 * MIB // e, 24 * MIB // e - 1):
@@ -63,7 +67,7 @@ def test_staged_matches_oracle_and_single_launch(orc, N, dtype, ratios, extra):
 
 def test_staged_in_place_repeated_and_cross_aliased_outputs(orc):
     N, dtype, ratios = 8, "f32", (100, 40)
-    n = _elems_for(4, 4, 5)                  # 4 distinct outputs of 32 MiB still select the pipeline
+    n = _elems_for(7, 4, 5)                  # 7 distinct outputs of 18.3 MiB still select the pipeline
     make = lambda: [inputs.node_buffer(dtype, n, 77, i, device=gu.DEV, std=1.0) for i in range(N)]
     ins = make()
     host = [inputs.to_host_storage(t) for t in ins]
@@ -76,12 +80,14 @@ def test_staged_in_place_repeated_and_cross_aliased_outputs(orc):
     torch.cuda.synchronize()
     gu.check_fused_against_oracle(orc, dtype, inputs.to_host_storage(work[3]), host, "in place")
     assert all(torch.equal(w, ref) for w in work)
-    # four distinct outputs, each named twice
-    four = [torch.empty_like(ref) for _ in range(4)]
-    assert nz.nz_allreduce_launches(N, n, ratios, dtype, "fused", 4) > 1
-    nz.nz_allreduce_sim(ins, n, ratios, dtype, "fused", [four[i % 4] for i in range(N)])
-    torch.cuda.synchronize()
-    assert all(torch.equal(t, ref) for t in four)
+    # seven distinct outputs, one of them named twice (the pipeline), then four, each named twice
+    # (one launch)
+    for k in (7, 4):
+        some = [torch.empty_like(ref) for _ in range(k)]
+        assert (nz.nz_allreduce_launches(N, n, ratios, dtype, "fused", k) > 1) == (k == 7)
+        nz.nz_allreduce_sim(ins, n, ratios, dtype, "fused", [some[i % k] for i in range(N)])
+        torch.cuda.synchronize()
+        assert all(torch.equal(t, ref) for t in some)
     # an output that is another node's input, whole: every input of an element is read before
     # any output of it is written
     work = make()
