@@ -774,12 +774,17 @@ __global__ __launch_bounds__(kThreads) void nz_ring_step(const RingArgs)
 // u - 1.  A rail with shorter segments has fewer pieces; the launch holds
 // workgroups only for the pieces a rail really has: rail k contributes pieces
 // piece_lo[k] .. piece_lo[k] + n - 1, n following from block0, with
-// N * g.tps[k] workgroups per piece (node, then tile).
+// N * g.tps[k] workgroups per piece (node, then tile) -- except the rail's
+// last piece, which is as short as it happens to be and gets
+// N * tps_last[k] workgroups, placed after those of the full pieces.
 struct RingWaveArgs {
-    RingArgs ring;                 // ring.step and ring.g.tile0 are not used
-    u32 wave;                      // w
-    u32 piece_lo[NZ_MAX_RAILS];    // first piece of each rail in this launch
-    u32 block0[NZ_MAX_RAILS + 1];  // first workgroup of each rail in this launch
+    RingArgs ring;                    // ring.step and ring.g.tile0 are not used
+    u32 wave;                         // w
+    u32 piece_lo[NZ_MAX_RAILS];       // first piece of each rail in this launch
+    u32 block0[NZ_MAX_RAILS + 1];     // first workgroup of each rail in this launch
+    u32 full_blocks[NZ_MAX_RAILS];    // workgroups of the rail's full-size pieces in this launch
+    u32 last_piece[NZ_MAX_RAILS];     // index of the rail's last piece
+    u32 tps_last[NZ_MAX_RAILS];       // tiles per segment of that piece
 };
 
 template <class T, int ITERS, bool REUSE>
@@ -789,11 +794,22 @@ __global__ __launch_bounds__(kThreads) void nz_ring_wave(const RingWaveArgs)
     const NZ_KARG RingArgs &a = w.ring;
     u32 rail = 0;
     while (rail + 1 < a.g.n_rails && blockIdx.x >= w.block0[rail + 1]) ++rail;
-    const u32 tps = a.g.tps[rail], N = a.g.n_nodes;
+    const u32 N = a.g.n_nodes;
     u32 rest = blockIdx.x - w.block0[rail];
-    const u32 tile = rest % tps;
-    rest /= tps;
-    const u32 r = rest % N, piece = w.piece_lo[rail] + rest / N;
+    u32 tile, r, piece;
+    if (rest < w.full_blocks[rail]) {
+        const u32 tps = a.g.tps[rail];
+        tile = rest % tps;
+        rest /= tps;
+        r = rest % N;
+        piece = w.piece_lo[rail] + rest / N;
+    } else {
+        rest -= w.full_blocks[rail];
+        const u32 tps = w.tps_last[rail];
+        tile = rest % tps;
+        r = rest / tps;
+        piece = w.last_piece[rail];
+    }
     const u32 u = w.wave - piece, half = N - 1;
     const u64 win_off = (u64)piece * a.g.win_len;
     if (u < half)

@@ -291,9 +291,19 @@ nz_status launch_ring_pipeline(const RingArgs &a, hipStream_t st, u64 n_pieces)
     const u32 R = a.g.n_rails, N = a.g.n_nodes;
     const u64 n_steps = 2ull * (N - 1);
     u64 rail_pieces[NZ_MAX_RAILS];  // a rail with shorter segments has fewer pieces
+    constexpr u64 kTileVecs = (u64)kRingIters * kThreads;
     for (u32 k = 0; k < R; ++k) {
         const u64 longest = a.g.q[k] + (a.g.rem[k] ? 1 : 0);
         rail_pieces[k] = (longest + a.g.win_len - 1) / a.g.win_len;
+        w.last_piece[k] = 0;
+        w.tps_last[k] = 1;
+        if (rail_pieces[k] == 0) continue;
+        // The last piece is as long as what the others leave; the tiles it can touch are
+        // bounded as build_geometry bounds those of a full piece.
+        const u64 last_len = longest - (rail_pieces[k] - 1) * a.g.win_len;
+        const u64 vecs = ((last_len << a.elem_shift) + 15) / 16 + 1;
+        w.last_piece[k] = (u32)(rail_pieces[k] - 1);
+        w.tps_last[k] = (u32)std::min<u64>((vecs + kTileVecs - 1) / kTileVecs + 1, a.g.tps[k]);
     }
     // Sizes first: nothing is launched if a launch would not fit a grid.
     for (int pass = 0; pass < 2; ++pass) {
@@ -304,8 +314,14 @@ nz_status launch_ring_pipeline(const RingArgs &a, hipStream_t st, u64 n_pieces)
                 const u64 started = std::min<u64>(wave + 1, rail_pieces[k]);  // pieces 0 .. started - 1 have begun
                 w.piece_lo[k] = (u32)lo;
                 w.block0[k] = (u32)blocks;
-                if (started > lo) blocks += (started - lo) * N * a.g.tps[k];
-                if (blocks > 0x7fffffffull) return NZ_ERR_UNSUPPORTED;
+                w.full_blocks[k] = 0;
+                if (started > lo) {
+                    const bool has_last = started == rail_pieces[k];
+                    const u64 full = (started - lo - (has_last ? 1 : 0)) * N * a.g.tps[k];
+                    blocks += full + (has_last ? (u64)N * w.tps_last[k] : 0);
+                    if (blocks > 0x7fffffffull) return NZ_ERR_UNSUPPORTED;
+                    w.full_blocks[k] = (u32)full;
+                }
             }
             w.block0[R] = (u32)blocks;
             if (pass == 0 || blocks == 0) continue;
