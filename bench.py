@@ -435,7 +435,10 @@ def main() -> int:
                          "algorithmic_bytes": alg_bytes[p]}
 
     head = "fused" if "fused" in parts else parts[0]
-    fused_launches = nz.nz_allreduce_launches(N, n, w.ratios, w.dtype, "fused", K)
+    used_outs = [outs[1]] if args.shared_output else outs
+    out_span = max(t.data_ptr() for t in used_outs) + S - min(t.data_ptr() for t in used_outs)
+    del used_outs                     # views of the arena: it must be free again before the plain allocations
+    fused_launches = nz.nz_allreduce_launches(N, n, w.ratios, w.dtype, "fused", K, out_span)
     launches = {"fused": fused_launches, "ring": 2 * (N - 1), "pack": R, "unpack": R, "rs": 1, "ag": 1,
                 "chunked": 2 * (N - 1), "failover": 2, "packed": R, "packed_out": R, "unpack_out": R}[head]
     fused_kernel = "nz_fused_stage" if fused_launches > 1 else "nz_fused_reduce_bcast"
@@ -443,8 +446,8 @@ def main() -> int:
     roofline = {
         "kernel": {"fused": fused_kernel, "ring": "nz_ring_step",
                    "pack": "nz_segment_copy", "unpack": "nz_segment_copy",
-                   "rs": "nz_fused_reduce_bcast", "ag": "nz_gather_bcast",
-                   "chunked": "nz_ring_wave", "failover": "nz_fused_reduce_bcast",
+                   "rs": "nz_fused_reduce_bcast", "ag": "nz_gather_range",
+                   "chunked": "nz_ring_wave", "failover": fused_kernel,
                    "packed": fused_kernel, "packed_out": fused_kernel, "unpack_out": "nz_segment_copy"}[head],
         "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),

@@ -121,7 +121,9 @@ nz_status nz_segment_map(const uint64_t *rail_off, uint32_t n_rails, uint32_t n_
  *     registers (int32: wrapping integer add) in a fixed blocked pairwise
  *     order that depends on n_nodes only, rounded once to `dtype` (nearest
  *     even) and written once to every distinct output buffer.  With fewer
- *     than seven distinct output buffers, or while the outputs together
+ *     than seven distinct output buffers (fewer than 17 if they span more
+ *     than NZ_HBM_REGION_BYTES of addresses, so that they cannot lie in one
+ *     memory region: see nz_hbm_place), or while the outputs together
  *     take less than 128 MiB, this is one launch whose unit of work is a
  *     tile of a segment.  Larger jobs run as a short pipeline of launches over
  *     pieces of at most 24 MiB of the participating rails: launch c sums
@@ -153,12 +155,15 @@ nz_status nz_allreduce_sim(const void *const *node_bufs, uint32_t n_nodes, uint6
 /*
  * How many kernel launches nz_allreduce_sim issues for these arguments (host
  * only; useful to size a HIP graph, and to turn a call's time into time per
- * launch).  n_distinct_outputs: how many different buffers out_bufs names.
+ * launch).  n_distinct_outputs: how many different buffers out_bufs names;
+ * outputs_span_bytes: from the start of the lowest of them to the end of the
+ * highest (0 if not known: taken to lie close together).
  * Same argument checks as nz_allreduce_sim as far as they apply.
  */
 nz_status nz_allreduce_launches(uint32_t n_nodes, uint64_t n_elems, const uint32_t *ratios,
                                 uint32_t n_rails, nz_dtype dtype, nz_mode mode,
-                                uint32_t n_distinct_outputs, uint64_t *launches);
+                                uint32_t n_distinct_outputs, uint64_t outputs_span_bytes,
+                                uint64_t *launches);
 
 /*
  * The two halves of the allreduce on their own.  (Sec. 2.1.1, Eq. 1: a ring

@@ -171,10 +171,22 @@ constexpr u64 kStageMinOutputBytes = NZ_STAGE_MIN_OUTPUT_BYTES;
 #define NZ_STAGE_MIN_OUTPUTS 7
 #endif
 constexpr u32 kStageMinOutputs = NZ_STAGE_MIN_OUTPUTS;
-bool staged_allreduce(u32 n_out, u64 active_bytes)
+// Output buffers that span more than the length of a memory region (see
+// nz_hbm_place) cannot all lie in one region.  Write streams spread over
+// regions are much less of a burden: the single launch then runs at 80-83 % of
+// peak whatever the number of outputs, which the pipeline only passes with
+// many of them (73 % with 7, 75 % with 8, 78 % with 12, 79 % with 16, 83 % with
+// 24 to 32, 85-86 % with 32 to 128 large ones).
+#ifndef NZ_STAGE_MIN_SPREAD_OUTPUTS
+#define NZ_STAGE_MIN_SPREAD_OUTPUTS 17
+#endif
+constexpr u32 kStageMinSpreadOutputs = NZ_STAGE_MIN_SPREAD_OUTPUTS;
+// out_span: bytes from the start of the lowest distinct output buffer to the
+// end of the highest.
+bool staged_allreduce(u32 n_out, u64 active_bytes, u64 out_span)
 {
-    return n_out >= kStageMinOutputs && active_bytes >= kStageMinBytes &&
-           active_bytes * n_out >= kStageMinOutputBytes;
+    const u32 min_outputs = out_span > NZ_HBM_REGION_BYTES ? kStageMinSpreadOutputs : kStageMinOutputs;
+    return n_out >= min_outputs && active_bytes >= kStageMinBytes && active_bytes * n_out >= kStageMinOutputBytes;
 }
 
 u64 round_up(u64 x, u64 m) { return (x + m - 1) / m * m; }
@@ -582,7 +594,13 @@ nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t
         u64 active_bytes = 0;
         for (u32 k = 0; k < n_rails; ++k)
             if (rail_mask >> k & 1u) active_bytes += (rail_off[k + 1] - rail_off[k]) << shift;
-        if (what == kAllreduce && staged_allreduce(a.n_out, active_bytes)) {
+        uintptr_t out_lo = UINTPTR_MAX, out_hi = 0;
+        for (u32 o = 0; o < a.n_out; ++o) {
+            const uintptr_t p = reinterpret_cast<uintptr_t>(a.out[o]);
+            out_lo = std::min(out_lo, p);
+            out_hi = std::max(out_hi, p + bytes);
+        }
+        if (what == kAllreduce && staged_allreduce(a.n_out, active_bytes, out_hi - out_lo)) {
             // Large message, several outputs: the staged pipeline.
             StageArgs sa;
             std::memset(&sa, 0, sizeof sa);
@@ -689,7 +707,8 @@ nz_status nz_allreduce_sim(const void *const *node_bufs, uint32_t n_nodes, uint6
 }
 
 nz_status nz_allreduce_launches(uint32_t n_nodes, uint64_t n_elems, const uint32_t *ratios, uint32_t n_rails,
-                                nz_dtype dtype, nz_mode mode, uint32_t n_distinct_outputs, uint64_t *launches)
+                                nz_dtype dtype, nz_mode mode, uint32_t n_distinct_outputs,
+                                uint64_t outputs_span_bytes, uint64_t *launches)
 {
     if (ratios == nullptr || launches == nullptr || n_nodes == 0 || n_rails == 0) return NZ_ERR_INVALID_ARG;
     const u32 eb = nz_dtype_bytes(dtype);
@@ -705,7 +724,7 @@ nz_status nz_allreduce_launches(uint32_t n_nodes, uint64_t n_elems, const uint32
         return NZ_OK;
     }
     const u64 bytes = n_elems * eb;
-    if (!staged_allreduce(n_distinct_outputs, bytes)) {
+    if (!staged_allreduce(n_distinct_outputs, bytes, outputs_span_bytes)) {
         *launches = 1;
         return NZ_OK;
     }

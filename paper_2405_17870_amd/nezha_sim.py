@@ -92,7 +92,7 @@ def load() -> ctypes.CDLL:
     lib.nz_balance_threshold.restype = i32
     lib.nz_balance_iterate.argtypes = [vp, u32, ctypes.c_double, u32, vp, vp, vp, vp]
     lib.nz_balance_iterate.restype = i32
-    lib.nz_allreduce_launches.argtypes = [u32, u64, vp, u32, i32, i32, u32, vp]
+    lib.nz_allreduce_launches.argtypes = [u32, u64, vp, u32, i32, i32, u32, u64, vp]
     lib.nz_allreduce_launches.restype = i32
     lib.nz_hbm_place.argtypes = [u64, vp, u32, u64, i32, u32, vp]
     lib.nz_hbm_place.restype = i32
@@ -235,12 +235,14 @@ def nz_allreduce_sim(node_bufs: Sequence, n_elems: int, ratios: Sequence[int], d
 
 
 def nz_allreduce_launches(n_nodes: int, n_elems: int, ratios: Sequence[int], dtype: str, mode: str,
-                          n_distinct_outputs: int) -> int:
-    """Kernel launches one nz_allreduce_sim call issues for these arguments.  Host only."""
+                          n_distinct_outputs: int, outputs_span_bytes: int = 0) -> int:
+    """Kernel launches one nz_allreduce_sim call issues for these arguments.  Host only.
+    outputs_span_bytes: from the start of the lowest output buffer to the end of the highest
+    (0: not known, taken to lie close together)."""
     lib = load()
     out = ctypes.c_uint64(0)
     _check(lib.nz_allreduce_launches(n_nodes, n_elems, _u32_array(ratios), len(ratios), DTYPE_CODE[dtype],
-                                     MODE_CODE[mode], n_distinct_outputs, ctypes.byref(out)))
+                                     MODE_CODE[mode], n_distinct_outputs, outputs_span_bytes, ctypes.byref(out)))
     return int(out.value)
 
 

@@ -108,8 +108,8 @@ extern "C" int nz_c_abi_checks(void)
         const uint32_t N = 31, ratios[2] = {100, 25};
         const uint64_t n = 1123457;
         uint64_t launches = 0;
-        REQUIRE(nz_allreduce_launches(N, n, ratios, 2, NZ_I32, NZ_FUSED, N, &launches) == NZ_OK && launches > 1);
-        REQUIRE(nz_allreduce_launches(N, n, ratios, 2, NZ_I32, NZ_FUSED, 1, &launches) == NZ_OK && launches == 1);
+        REQUIRE(nz_allreduce_launches(N, n, ratios, 2, NZ_I32, NZ_FUSED, N, 0, &launches) == NZ_OK && launches > 1);
+        REQUIRE(nz_allreduce_launches(N, n, ratios, 2, NZ_I32, NZ_FUSED, 1, 0, &launches) == NZ_OK && launches == 1);
         std::vector<std::vector<int32_t>> in(N);
         for (uint32_t i = 0; i < N; ++i) in[i].assign(n, (int32_t)(1u << i));
         std::vector<int32_t> expect(n, 0x7fffffff);

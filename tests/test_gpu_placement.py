@@ -1,9 +1,13 @@
 """The harness's HBM arena hands out aligned, disjoint tensors inside the requested regions."""
+import numpy as np
 import pytest
 import torch
 
+from paper_2405_17870_amd import inputs
 from paper_2405_17870_amd import nezha_sim as nz
 from paper_2405_17870_amd import placement
+
+import gpu_util as gu
 
 pytestmark = pytest.mark.gpu
 
@@ -38,3 +42,36 @@ def test_arena_regions_alignment_and_use():
     assert all(bool((o == 10.0).all()) for o in outs)
     with pytest.raises(RuntimeError):
         arena.alloc(placement.REGION_BYTES, torch.uint8, 1)            # does not fit what is left
+
+
+def test_outputs_spread_over_regions_take_the_single_launch(orc):
+    """Up to 16 output buffers that span more than a region's length are written by the
+    single-launch kernel however large the job (with plain allocations the same job runs as
+    the pipeline); 17 spread outputs take the pipeline again.  Same bits either way, and the
+    oracle's sums."""
+    arena = placement.try_arena("cuda:0")
+    if arena is None:
+        pytest.skip("not enough free HBM for a three-region arena")
+    for N, dtype, ratios in ((8, "bf16", (100, 100, 40)), (16, "f32", (100, 40)), (17, "f32", (3, 1))):
+        tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+        e = inputs.ELEM_BYTES[dtype]
+        n = -(-(128 << 20) // (N * e)) + 77
+        print(f"spread outputs N={N} {dtype} n={n}", flush=True)
+        ins = [arena.alloc(n, tdt, 0) for _ in range(N)]
+        for i, t in enumerate(ins):
+            t.copy_(inputs.node_buffer(dtype, n, 900 + N, i, device="cuda:0", std=1e-2))
+        outs = arena.alloc_striped(N, n, tdt)
+        for t in outs:
+            t.zero_()
+        span = max(t.data_ptr() for t in outs) + n * e - min(t.data_ptr() for t in outs)
+        assert span > nz.NZ_HBM_REGION_BYTES
+        assert (nz.nz_allreduce_launches(N, n, ratios, dtype, "fused", N, span) == 1) == (N <= 16)
+        assert nz.nz_allreduce_launches(N, n, ratios, dtype, "fused", N) > 1
+        nz.nz_allreduce_sim(ins, n, ratios, dtype, "fused", outs)
+        near = [torch.zeros_like(t) for t in ins]                       # plain allocations: the pipeline
+        nz.nz_allreduce_sim(ins, n, ratios, dtype, "fused", near)
+        torch.cuda.synchronize()
+        host = [inputs.to_host_storage(t) for t in ins]
+        gu.check_fused_against_oracle(orc, dtype, inputs.to_host_storage(outs[N - 1]), host, f"spread N={N}")
+        for a, b in zip(outs, near):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))

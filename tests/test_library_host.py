@@ -225,3 +225,19 @@ def test_hbm_place_spreads_written_buffers_and_keeps_read_buffers_together():
     with pytest.raises(nz.NezhaSimError):                          # an arena that ends inside region 0's margin of region 1
         nz.nz_hbm_place(90 * GIB, small, 1, each, False, 1)
     assert list(nz.nz_hbm_place(90 * GIB, small, 2, each, False, 0)) == [0, 640 << 20]
+
+
+def test_launch_count_follows_the_rule_for_the_staged_pipeline():
+    """One launch below 7 distinct outputs, below 128 MiB of outputs, or (up to 16 outputs) when
+    they span more than a memory region; otherwise one launch per piece of at most 24 MiB plus one."""
+    MIB = 1 << 20
+    n = 64 * MIB // 4                                   # 64 MiB per node, fp32
+    count = lambda N, K, span=0, n=n: nz.nz_allreduce_launches(N, n, (100, 40), "f32", "fused", K, span)
+    assert count(8, 8) == 3 + 1                         # 64 MiB = 3 pieces of at most 24 MiB
+    assert count(8, 6) == 1 and count(8, 7) == 4 and count(8, 1) == 1
+    assert count(8, 8, n=(128 * MIB // 8 - 256) // 4) == 1          # just under 128 MiB of outputs
+    assert count(8, 8, n=128 * MIB // 8 // 4) == 1 + 1              # 16 MiB per node: one piece
+    far = nz.NZ_HBM_REGION_BYTES + 1
+    assert count(8, 8, far) == 1 and count(16, 16, far) == 1 and count(17, 17, far) == 4
+    assert count(16, 16, nz.NZ_HBM_REGION_BYTES) == 4   # exactly a region's length can still be one region
+    assert nz.nz_allreduce_launches(8, n, (100, 40), "f32", "ring-stepwise", 8) == 14
