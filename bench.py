@@ -441,13 +441,13 @@ def main() -> int:
     fused_launches = nz.nz_allreduce_launches(N, n, w.ratios, w.dtype, "fused", K, out_span)
     launches = {"fused": fused_launches, "ring": 2 * (N - 1), "pack": R, "unpack": R, "rs": 1, "ag": 1,
                 "chunked": 2 * (N - 1), "failover": 2, "packed": R, "packed_out": R, "unpack_out": R}[head]
-    fused_kernel = "nz_fused_stage" if fused_launches > 1 else "nz_fused_reduce_bcast"
+    fused_kernel = "nz_fused_stage" if fused_launches > 1 else "nz_fused_flat"
     achieved = part_stats[head]["hbm_GBps"]
     roofline = {
         "kernel": {"fused": fused_kernel, "ring": "nz_ring_step",
                    "pack": "nz_segment_copy", "unpack": "nz_segment_copy",
                    "rs": "nz_fused_reduce_bcast", "ag": "nz_gather_range",
-                   "chunked": "nz_ring_wave", "failover": fused_kernel,
+                   "chunked": "nz_ring_wave", "failover": "nz_fused_stage" if fused_launches > 1 else "nz_fused_reduce_bcast",
                    "packed": fused_kernel, "packed_out": fused_kernel, "unpack_out": "nz_segment_copy"}[head],
         "bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(achieved / HBM_PEAK_GBS, 4),

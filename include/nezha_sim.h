@@ -116,7 +116,7 @@ nz_status nz_segment_map(const uint64_t *rail_off, uint32_t n_rails, uint32_t n_
  * for every element x, the sum over i of node_bufs[i][x].
  *
  * The message is partitioned by nz_rail_partition(ratios) and each rail by
- * nz_segment_map; segment j of a rail is the unit of work.
+ * nz_segment_map; segment j of a rail is the unit of the ring schedule.
  *   NZ_FUSED: every element is read once from all nodes, summed in fp32
  *     registers (int32: wrapping integer add) in a fixed blocked pairwise
  *     order that depends on n_nodes only, rounded once to `dtype` (nearest
@@ -124,9 +124,10 @@ nz_status nz_segment_map(const uint64_t *rail_off, uint32_t n_rails, uint32_t n_
  *     than seven distinct output buffers (fewer than 17 if they span more
  *     than NZ_HBM_REGION_BYTES of addresses, so that they cannot lie in one
  *     memory region: see nz_hbm_place), or while the outputs together
- *     take less than 128 MiB, this is one launch whose unit of work is a
- *     tile of a segment.  Larger jobs run as a short pipeline of launches over
- *     pieces of at most 24 MiB of the participating rails: launch c sums
+ *     take less than 128 MiB, this is one launch over the whole message
+ *     (the sums do not depend on where rails and segments begin; the unit
+ *     of work is a 4 KiB tile).  Larger jobs run as a short pipeline of
+ *     launches over pieces of at most 24 MiB of the participating rails: launch c sums
  *     piece c into one of the output buffers (the one farthest from the
  *     inputs) and copies piece c - 1 from there (re-read through the L2
  *     caches) to the other output buffers one after the other, because a

@@ -517,16 +517,16 @@ __device__ __forceinline__ typename P::raw_t reduce_at(NodeTable in, u32 N, u64 
 // a buffer that depends on the workgroup, so that workgroups running at the
 // same time write to different buffers.
 template <class P, bool CACHED>
-__device__ __forceinline__ void bcast_at(const NZ_KARG FusedArgs &a, u64 byte_off, u32 out_begin, u32 out_end,
+__device__ __forceinline__ void bcast_at(OutTable out, u64 byte_off, u32 out_begin, u32 out_end,
                                          typename P::raw_t packed)
 {
     const u32 K = out_end - out_begin;
     u32 o = out_begin + blockIdx.x % K;
     for (u32 i = 0; i < K; ++i) {
         if (CACHED)
-            P::store_for_reuse(a.out[o], byte_off, packed);
+            P::store_for_reuse(out[o], byte_off, packed);
         else
-            P::store(a.out[o], byte_off, packed);
+            P::store(out[o], byte_off, packed);
         if (++o == out_end) o = out_begin;
     }
 }
@@ -535,21 +535,18 @@ template <class T, class P, int CLASS, bool CACHED>
 __device__ __forceinline__ void reduce_bcast_at(const NZ_KARG FusedArgs &a, u64 byte_off, u32 out_begin,
                                                 u32 out_end)
 {
-    bcast_at<P, CACHED>(a, byte_off, out_begin, out_end,
+    bcast_at<P, CACHED>(a.out, byte_off, out_begin, out_end,
                         reduce_at<T, P, CLASS, CACHED>(a.in, a.g.n_nodes, byte_off));
 }
 
-// The grid has two kinds of workgroups.  The first g.tile0[n_rails] of them
-// each take one aligned tile of VPT x 256 vectors of one segment and handle
-// the vectors that lie wholly inside it.  They are followed by one workgroup
-// per (rail, segment) for the elements that share a 16-byte vector with a
-// neighbouring segment or with the end of the buffer: one thread per element.
-// VPT, vectors per thread: with few nodes a thread has few loads of its own
-// to keep in flight, so it takes several vectors and issues the loads of all
-// of them before the first store (used for jobs that run out of the
-// last-level cache, where latency is what bounds them; a job that streams
-// from HBM is no faster for it).
-template <class T, int CLASS, bool CACHED, int VPT>
+// The segment-wise form: the reduce-scatter half (segment j goes to its owner
+// alone) and allreduces over some of the rails only.  The grid has two kinds
+// of workgroups.  The first g.tile0[n_rails] of them each take one aligned
+// tile of 256 vectors of one segment and handle the vectors that lie wholly
+// inside it.  They are followed by one workgroup per (rail, segment) for the
+// elements that share a 16-byte vector with a neighbouring segment or with
+// the end of the buffer: one thread per element.
+template <class T, int CLASS, bool CACHED>
 __global__ __launch_bounds__(kThreads) void nz_fused_reduce_bcast(const FusedArgs)
 {
     const NZ_KARG FusedArgs &a = kernel_args<FusedArgs>();
@@ -557,25 +554,14 @@ __global__ __launch_bounds__(kThreads) void nz_fused_reduce_bcast(const FusedArg
     if (blockIdx.x < n_tiles) {
         u32 rail, seg, tile;
         decode_block(a.g, blockIdx.x, rail, seg, tile);
-        const SegTile t = segment_tile<VPT * kThreads>(a.g, rail, seg, tile, T::kShift);
+        const SegTile t = segment_tile<kThreads>(a.g, rail, seg, tile, T::kShift);
         const u64 full_lo = (t.b0 + 15) >> 4, full_hi = t.b1 >> 4;
         const u64 lo = t.vec_lo > full_lo ? t.vec_lo : full_lo;
         const u64 hi = t.vec_hi < full_hi ? t.vec_hi : full_hi;
+        const u64 vec = t.tile_base + threadIdx.x;
         const u32 owner = (seg == 0 ? a.g.n_nodes : seg) - 1;
         const u32 o0 = a.owner_only ? owner : 0, o1 = a.owner_only ? owner + 1 : a.n_out;
-        typename VecPacket<T>::raw_t packed[VPT];
-        bool mine[VPT];
-#pragma unroll
-        for (int it = 0; it < VPT; ++it) {
-            const u64 vec = t.tile_base + (u64)it * kThreads + threadIdx.x;
-            mine[it] = vec >= lo && vec < hi;
-            if (mine[it]) packed[it] = reduce_at<T, VecPacket<T>, CLASS, CACHED>(a.in, a.g.n_nodes, vec << 4);
-        }
-#pragma unroll
-        for (int it = 0; it < VPT; ++it) {
-            const u64 vec = t.tile_base + (u64)it * kThreads + threadIdx.x;
-            if (mine[it]) bcast_at<VecPacket<T>, CACHED>(a, vec << 4, o0, o1, packed[it]);
-        }
+        if (vec >= lo && vec < hi) reduce_bcast_at<T, VecPacket<T>, CLASS, CACHED>(a, vec << 4, o0, o1);
         return;
     }
     const u32 e = blockIdx.x - n_tiles;
@@ -594,6 +580,45 @@ __global__ __launch_bounds__(kThreads) void nz_fused_reduce_bcast(const FusedArg
     if (part == 0 && t.b0 + eoff < head_end) reduce_bcast_at<T, ElemPacket<T>, CLASS, CACHED>(a, t.b0 + eoff, o0, o1);
     if (part == 1 && tail_beg + eoff < t.b1)
         reduce_bcast_at<T, ElemPacket<T>, CLASS, CACHED>(a, tail_beg + eoff, o0, o1);
+}
+
+// The allreduce over the whole message in one launch.  Every element's sum
+// goes to every output, so nothing here depends on where rails and segments
+// begin: a workgroup takes VPT x 256 consecutive vectors of the buffers, and
+// the last vector, if the message ends inside it, is done element by element.
+// VPT, vectors per thread: with few nodes a thread has few loads of its own
+// to keep in flight, so it takes several vectors and issues the loads of all
+// of them before the first store (used for jobs that run out of the
+// last-level cache, where latency is what bounds them; a job that streams
+// from HBM is no faster for it).
+struct FlatArgs {
+    u64 bytes;  // of every buffer
+    u32 n_nodes, n_out;
+    const void *in[NZ_MAX_NODES];
+    void *out[NZ_MAX_NODES];
+};
+
+template <class T, int CLASS, bool CACHED, int VPT>
+__global__ __launch_bounds__(kThreads) void nz_fused_flat(const FlatArgs)
+{
+    const NZ_KARG FlatArgs &a = kernel_args<FlatArgs>();
+    typename VecPacket<T>::raw_t packed[VPT];
+#pragma unroll
+    for (int it = 0; it < VPT; ++it) {
+        const u64 b0 = (((u64)blockIdx.x * VPT + it) * kThreads + threadIdx.x) << 4;
+        if (b0 + 16 <= a.bytes) packed[it] = reduce_at<T, VecPacket<T>, CLASS, CACHED>(a.in, a.n_nodes, b0);
+    }
+#pragma unroll
+    for (int it = 0; it < VPT; ++it) {
+        const u64 b0 = (((u64)blockIdx.x * VPT + it) * kThreads + threadIdx.x) << 4;
+        if (b0 + 16 <= a.bytes) {
+            bcast_at<VecPacket<T>, CACHED>(a.out, b0, 0, a.n_out, packed[it]);
+        } else if (b0 < a.bytes) {
+            for (u64 b = b0; b < a.bytes; b += sizeof(typename T::elem_t))
+                bcast_at<ElemPacket<T>, CACHED>(a.out, b, 0, a.n_out,
+                                                reduce_at<T, ElemPacket<T>, CLASS, CACHED>(a.in, a.n_nodes, b));
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------

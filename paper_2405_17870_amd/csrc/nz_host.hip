@@ -108,7 +108,24 @@ u64 build_geometry(RailGeom &g, const u64 *rail_off, u32 n_rails, u32 n_nodes, u
 // inputs in cache and leaves its results there for whoever reads them next.
 constexpr u64 kFusedCachedBytes = 128ull << 20;
 
-// Vectors per thread of the single-launch fused kernel for a job that runs out
+template <class T, bool CACHED>
+hipError_t launch_fused_class(const FusedArgs &a, u32 blocks, hipStream_t st)
+{
+    return a.g.n_nodes <= 8    ? launch(nz_fused_reduce_bcast<T, kUpTo8, CACHED>, blocks, a, st)
+           : a.g.n_nodes <= 32 ? launch(nz_fused_reduce_bcast<T, kUpTo32, CACHED>, blocks, a, st)
+                               : launch(nz_fused_reduce_bcast<T, kAnyN, CACHED>, blocks, a, st);
+}
+
+// moved_bytes: what the launch reads and writes.
+template <class T>
+nz_status launch_fused(const FusedArgs &a, u32 blocks, hipStream_t st, u64 moved_bytes)
+{
+    const hipError_t e = moved_bytes <= kFusedCachedBytes ? launch_fused_class<T, true>(a, blocks, st)
+                                                          : launch_fused_class<T, false>(a, blocks, st);
+    return e == hipSuccess ? NZ_OK : hip_failed(e, "fused reduce launch");
+}
+
+// Vectors per thread of the whole-message fused kernel for a job that runs out
 // of the last-level cache: a thread should have about eight loads of its own in
 // flight, which the blocked sum provides from five nodes on.  (A job that
 // streams from HBM gains nothing from more: measured 1 to 3 % slower.)
@@ -121,8 +138,7 @@ constexpr u64 kFusedCachedBytes = 128ull << 20;
 #ifndef NZ_FUSED_VPT_MIN_BLOCKS
 #define NZ_FUSED_VPT_MIN_BLOCKS 2048  // eight workgroups per compute unit
 #endif
-// `bytes`: what the launch reduces, per node.  A small job keeps small tiles so
-// that it still spreads over the whole chip.
+// A small job keeps small tiles so that it still spreads over the whole chip.
 u32 fused_vpt(u32 n_nodes, u64 bytes, bool cached)
 {
     if (!cached) return 1;
@@ -132,23 +148,26 @@ u32 fused_vpt(u32 n_nodes, u64 bytes, bool cached)
 }
 
 template <class T, bool CACHED>
-hipError_t launch_fused_class(const FusedArgs &a, u32 blocks, hipStream_t st)
+hipError_t launch_flat_class(const FlatArgs &a, u32 blocks, hipStream_t st)
 {
-    return a.g.n_nodes <= 8    ? launch(nz_fused_reduce_bcast<T, kUpTo8, CACHED, 1>, blocks, a, st)
-           : a.g.n_nodes <= 32 ? launch(nz_fused_reduce_bcast<T, kUpTo32, CACHED, 1>, blocks, a, st)
-                               : launch(nz_fused_reduce_bcast<T, kAnyN, CACHED, 1>, blocks, a, st);
+    return a.n_nodes <= 8    ? launch(nz_fused_flat<T, kUpTo8, CACHED, 1>, blocks, a, st)
+           : a.n_nodes <= 32 ? launch(nz_fused_flat<T, kUpTo32, CACHED, 1>, blocks, a, st)
+                             : launch(nz_fused_flat<T, kAnyN, CACHED, 1>, blocks, a, st);
 }
 
-// moved_bytes: what the launch reads and writes; vpt: as chosen by fused_vpt
-// for the same job (the geometry in `a` is built for that tile size).
+// The allreduce over the whole message in one launch.
 template <class T>
-nz_status launch_fused(const FusedArgs &a, u32 blocks, hipStream_t st, u64 moved_bytes, u32 vpt)
+nz_status launch_flat(const FlatArgs &a, hipStream_t st)
 {
-    const bool cached = moved_bytes <= kFusedCachedBytes;
-    const hipError_t e = vpt == 4   ? launch(nz_fused_reduce_bcast<T, kUpTo8, true, 4>, blocks, a, st)
-                         : vpt == 2 ? launch(nz_fused_reduce_bcast<T, kUpTo8, true, 2>, blocks, a, st)
-                         : cached   ? launch_fused_class<T, true>(a, blocks, st)
-                                    : launch_fused_class<T, false>(a, blocks, st);
+    const bool cached = a.bytes * (a.n_nodes + a.n_out) <= kFusedCachedBytes;
+    const u32 vpt = fused_vpt(a.n_nodes, a.bytes, cached);
+    const u64 tile_bytes = (u64)vpt * kThreads * 16;
+    const u64 blocks = (a.bytes + tile_bytes - 1) / tile_bytes;
+    if (blocks > 0x7fffffffull) return NZ_ERR_UNSUPPORTED;
+    const hipError_t e = vpt == 4   ? launch(nz_fused_flat<T, kUpTo8, true, 4>, (u32)blocks, a, st)
+                         : vpt == 2 ? launch(nz_fused_flat<T, kUpTo8, true, 2>, (u32)blocks, a, st)
+                         : cached   ? launch_flat_class<T, true>(a, (u32)blocks, st)
+                                    : launch_flat_class<T, false>(a, (u32)blocks, st);
     return e == hipSuccess ? NZ_OK : hip_failed(e, "fused reduce launch");
 }
 
@@ -640,17 +659,32 @@ nz_status run_collective(Collective what, const void *const *node_bufs, uint32_t
             }
             return NZ_ERR_INVALID_ARG;
         }
-        const u64 moved = active_bytes * (n_nodes + (a.owner_only ? 1 : a.n_out));
-        const u32 vpt = fused_vpt(n_nodes, active_bytes, moved <= kFusedCachedBytes);
-        u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, vpt * kThreads, rail_mask);
+        if (what == kAllreduce && active_bytes == bytes) {
+            // Every rail takes part: the sums do not depend on where rails and segments begin.
+            FlatArgs fa;
+            fa.bytes = bytes;
+            fa.n_nodes = n_nodes;
+            fa.n_out = a.n_out;
+            for (u32 i = 0; i < n_nodes; ++i) fa.in[i] = a.in[i];
+            for (u32 i = 0; i < a.n_out; ++i) fa.out[i] = a.out[i];
+            switch (dtype) {
+            case NZ_F32: return launch_flat<TF32>(fa, st);
+            case NZ_I32: return launch_flat<TI32>(fa, st);
+            case NZ_BF16: return launch_flat<TBF16>(fa, st);
+            case NZ_F16: return launch_flat<TF16>(fa, st);
+            }
+            return NZ_ERR_INVALID_ARG;
+        }
+        u64 blocks = build_geometry(a.g, rail_off, n_rails, n_nodes, shift, kThreads, rail_mask);
         if (blocks == 0) return NZ_ERR_UNSUPPORTED;
         if (blocks == kNothingToDo) return NZ_OK;
         blocks += (u64)n_rails * n_nodes;  // the workgroups for segment edges
+        const u64 moved = active_bytes * (n_nodes + (a.owner_only ? 1 : a.n_out));
         switch (dtype) {
-        case NZ_F32: return launch_fused<TF32>(a, (u32)blocks, st, moved, vpt);
-        case NZ_I32: return launch_fused<TI32>(a, (u32)blocks, st, moved, vpt);
-        case NZ_BF16: return launch_fused<TBF16>(a, (u32)blocks, st, moved, vpt);
-        case NZ_F16: return launch_fused<TF16>(a, (u32)blocks, st, moved, vpt);
+        case NZ_F32: return launch_fused<TF32>(a, (u32)blocks, st, moved);
+        case NZ_I32: return launch_fused<TI32>(a, (u32)blocks, st, moved);
+        case NZ_BF16: return launch_fused<TBF16>(a, (u32)blocks, st, moved);
+        case NZ_F16: return launch_fused<TF16>(a, (u32)blocks, st, moved);
         }
         return NZ_ERR_INVALID_ARG;
     }
