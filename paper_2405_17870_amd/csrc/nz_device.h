@@ -976,10 +976,6 @@ __global__ __launch_bounds__(kThreads) void nz_gather_bcast(const GatherArgs)
 // ---------------------------------------------------------------------------
 
 constexpr int kCopyMaxRuns = 64;  // runs per launch; longer lists take several launches
-#ifndef NZ_COPY_ITERS
-#define NZ_COPY_ITERS 2
-#endif
-constexpr int kCopyIters = NZ_COPY_ITERS;  // 256-vector sub-tiles per workgroup
 
 // One run: len bytes from src_off in every source buffer to dst_off in the
 // matching destination buffer.  All three are multiples of the element size.
@@ -991,6 +987,7 @@ struct CopyArgs {
     u32 n_runs;
     u32 elem_bytes;
     u32 n_nodes;
+    u32 node_major;  // workgroup order: 1 = one node's runs after the other, 0 = node index fastest
     const void *src[NZ_MAX_NODES];
     void *dst[NZ_MAX_NODES];
 };
@@ -1014,16 +1011,30 @@ __device__ __forceinline__ void copy_elem(char *dst, const char *src)
 // either buffer.
 //
 // ALIGNED_ONLY: the host saw that every run of the launch has shift == 0 (a
-// whole rail always has); the exchange path is then compiled out.
-template <bool ALIGNED_ONLY>
+// whole rail always has); the exchange path is then compiled out.  ITERS:
+// 256-vector sub-tiles per workgroup.
+//
+// Workgroup order.  Node-major: the chip works through one node's buffers at a
+// time, one read stream and one write stream, which is what the memory system
+// handles best when all buffers lie close together.  Node index fastest: the
+// workgroups in flight cover the same tiles of many nodes' buffers; better
+// when the destinations are spread over the memory regions and the sources
+// are not, because the writes then load all regions at once.
+template <bool ALIGNED_ONLY, int ITERS>
 __global__ __launch_bounds__(kThreads) void nz_segment_copy(const CopyArgs)
 {
     const NZ_KARG CopyArgs &a = kernel_args<CopyArgs>();
+    constexpr int kCopyIters = ITERS;
 
-    // Node index fastest: the workgroups in flight at one time cover the same
-    // tiles of many nodes' buffers rather than one buffer end to end.
-    const u32 per_node = blockIdx.x / a.n_nodes;
-    const u32 node = blockIdx.x - per_node * a.n_nodes;
+    u32 node, per_node;
+    if (a.node_major) {
+        const u32 per_node_total = a.tile0[a.n_runs];
+        node = blockIdx.x / per_node_total;
+        per_node = blockIdx.x - node * per_node_total;
+    } else {
+        per_node = blockIdx.x / a.n_nodes;
+        node = blockIdx.x - per_node * a.n_nodes;
+    }
     u32 run = 0;
     for (u32 span = a.n_runs; span > 1;) {  // last run whose first workgroup is <= per_node
         const u32 half = span >> 1;
