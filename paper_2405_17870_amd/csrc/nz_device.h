@@ -76,8 +76,11 @@ struct SegTile {
 __device__ __forceinline__ void decode_block(const NZ_KARG RailGeom &g, u32 block, u32 &rail, u32 &idx,
                                              u32 &tile)
 {
+    // tile0 never decreases, so the rail is the number of later rails that start at or before
+    // this workgroup; counted without a loop so that the loads do not wait for one another.
     u32 k = 0;
-    while (k + 1 < g.n_rails && block >= g.tile0[k + 1]) ++k;
+#pragma unroll
+    for (u32 i = 1; i < NZ_MAX_RAILS; ++i) k += (i < g.n_rails && block >= g.tile0[i]) ? 1u : 0u;
     const u32 local = block - g.tile0[k];
     rail = k;
     idx = local / g.tps[k];
@@ -817,8 +820,9 @@ __global__ __launch_bounds__(kThreads) void nz_ring_wave(const RingWaveArgs)
 {
     const NZ_KARG RingWaveArgs &w = kernel_args<RingWaveArgs>();
     const NZ_KARG RingArgs &a = w.ring;
-    u32 rail = 0;
-    while (rail + 1 < a.g.n_rails && blockIdx.x >= w.block0[rail + 1]) ++rail;
+    u32 rail = 0;  // block0 never decreases: count the later rails that start at or before this workgroup
+#pragma unroll
+    for (u32 i = 1; i < NZ_MAX_RAILS; ++i) rail += (i < a.g.n_rails && blockIdx.x >= w.block0[i]) ? 1u : 0u;
     const u32 N = a.g.n_nodes;
     u32 rest = blockIdx.x - w.block0[rail];
     u32 tile, r, piece;
@@ -872,8 +876,9 @@ __global__ __launch_bounds__(kThreads) void nz_gather_range(const GatherRangeArg
     constexpr int TILE = ITERS * kThreads;
     typedef typename T::elem_t elem_t;
     const u32 N = a.g.n_nodes;
-    u32 rail = 0;
-    while (rail + 1 < a.g.n_rails && blockIdx.x >= a.g.tile0[rail + 1]) ++rail;
+    u32 rail = 0;  // tile0 never decreases: count the later rails that start at or before this workgroup
+#pragma unroll
+    for (u32 i = 1; i < NZ_MAX_RAILS; ++i) rail += (i < a.g.n_rails && blockIdx.x >= a.g.tile0[i]) ? 1u : 0u;
     const u32 tps = a.g.tps[rail];
     u32 rest = blockIdx.x - a.g.tile0[rail];
     const u32 tile = rest % tps;
