@@ -117,3 +117,39 @@ def test_staged_failover_runs_the_surviving_spans_then_the_failed_rail(orc, fail
         assert torch.equal(o.view(torch.uint8), r.view(torch.uint8))
     host = [inputs.to_host_storage(t[-300_000:]) for t in ins]
     gu.check_fused_against_oracle(orc, dtype, inputs.to_host_storage(outs[0][-300_000:]), host, "failover tail")
+
+
+MI = 1 << 20
+# (N, dtype, distinct outputs, elements): sizes the library's rule sends to the several-vectors
+# form of the whole-message kernel -- at most 4 nodes, all bytes of the call within 128 MiB, and
+# at least 2048 workgroups of 2 (16 MiB per node) or 4 (2 nodes, 32 MiB per node) vectors per thread
+FEW_NODES_CACHED = [
+    (2, "f32", 2, 4 * MI + 5),        # 16 MiB per node, two vectors per thread
+    (2, "bf16", 1, 17 * MI + 3),      # 34 MiB per node, one shared output: four vectors per thread
+    (2, "i32", 2, 8 * MI),            # exactly 32 MiB: four vectors per thread, no ragged end
+    (3, "i32", 3, 4 * MI + MI // 2 + 7),   # 18 MiB per node, two vectors per thread
+    (4, "f16", 1, 9 * MI + 1),        # 18 MiB per node, one shared output: two vectors per thread
+]
+
+
+@pytest.mark.parametrize("N,dtype,K,n", FEW_NODES_CACHED)
+def test_cache_resident_jobs_of_few_nodes(orc, N, dtype, K, n):
+    """Every sum against the oracle, inputs untouched, all outputs the same bits."""
+    ratios = (100, 40)
+    e = inputs.ELEM_BYTES[dtype]
+    assert (N + K) * n * e <= 128 * MI and n * e >= 16 * MI
+    print(f"few nodes, cache resident: N={N} {dtype} K={K} n={n}", flush=True)
+    ins = [inputs.node_buffer(dtype, n, 1300 + N, i, device=gu.DEV, std=1e-2) for i in range(N)]
+    if dtype not in ("i32",):
+        ins[0][n - 1] = float("inf")
+        ins[N - 1][n - 2] = float("nan")
+    host = [inputs.to_host_storage(t) for t in ins]
+    distinct = [torch.full_like(ins[0], 7) for _ in range(K)]
+    nz.nz_allreduce_sim(ins, n, ratios, dtype, "fused", [distinct[i % K] for i in range(N)])
+    torch.cuda.synchronize()
+    got = inputs.to_host_storage(distinct[0])
+    gu.check_fused_against_oracle(orc, dtype, got, host, f"few nodes N={N}")
+    for o in distinct[1:]:
+        assert torch.equal(o.view(torch.uint8), distinct[0].view(torch.uint8))
+    for t, h in zip(ins, host):
+        assert inputs.to_host_storage(t).tobytes() == h.tobytes()
