@@ -80,6 +80,15 @@ def test_pack_unpack_random_lists(orc, e):
         _case(orc, N, ratios, n, e, rnd.randrange(R), ids, capacity_slack=rnd.choice([0, 2 * e, 640]))
 
 
+def test_pack_unpack_launches_of_2_gib_and_more(orc):
+    """From 2 GiB per launch on the copy kernel works on 4 KB tiles; here with runs that are not
+    aligned with their place in the send buffer (odd segment lengths, segments out of order)
+    and, for the whole rail in order, with one aligned run per node."""
+    N, n = 4, 4 * 34_000_001 + 1
+    _case(orc, N, (1,), n, 2, 0, [2, 1, 0, 3])
+    _case(orc, N, (1,), n, 2, 0, [0, 1, 2, 3])
+
+
 def test_pack_errors(orc):
     N, n, e = 4, 10_000, 4
     seg = nz.nz_segment_map(nz.nz_rail_partition(n, e, (1, 1)), N)

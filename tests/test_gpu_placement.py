@@ -75,3 +75,32 @@ def test_outputs_spread_over_regions_take_the_single_launch(orc):
         gu.check_fused_against_oracle(orc, dtype, inputs.to_host_storage(outs[N - 1]), host, f"spread N={N}")
         for a, b in zip(outs, near):
             assert torch.equal(a.view(torch.uint8), b.view(torch.uint8))
+
+
+def test_pack_into_send_buffers_spread_over_regions(orc):
+    """Send buffers that span more than a region while the node buffers do not: the copy kernel
+    then runs with the node index fastest.  Whole rail (aligned runs) and the order a node sends
+    in (runs not aligned with their place in the send buffer); bytes against the oracle."""
+    arena = placement.try_arena("cuda:0")
+    if arena is None:
+        pytest.skip("not enough free HBM for a three-region arena")
+    N, ratios, n, e = 8, (100, 40), 700_001, 2
+    seg = nz.nz_segment_map(nz.nz_rail_partition(n, e, ratios), N)
+    rng = np.random.default_rng(5)
+    host = [rng.integers(0, 256, size=n * e, dtype=np.uint8) for _ in range(N)]
+    node = [arena.alloc(n, torch.bfloat16, 0) for _ in range(N)]
+    for t, h in zip(node, host):
+        t.view(torch.uint8).copy_(torch.from_numpy(h))
+    for rail, ids in ((0, list(range(N))), (1, [(3 - s) % N for s in range(N)]), (0, [5, 2, 7])):
+        total = sum(int(seg[rail, j + 1] - seg[rail, j]) for j in ids) * e
+        send = arena.alloc_striped(N, total // e + 64, torch.bfloat16)
+        assert max(t.data_ptr() for t in send) - min(t.data_ptr() for t in send) > nz.NZ_HBM_REGION_BYTES
+        for t in send:
+            t.view(torch.uint8).fill_(0xEE)
+        assert nz.nz_pack(node, seg, rail, ids, e, send, total + 128) == total
+        torch.cuda.synchronize()
+        for m in range(N):
+            want, nbytes = orc.pack(host[m], seg, rail, ids, e)
+            got = send[m].view(torch.uint8).cpu().numpy()
+            assert nbytes == total and np.array_equal(got[:total], want), (rail, m)
+            assert (got[total:] == 0xEE).all()
