@@ -66,6 +66,9 @@ def parse_args():
     p.add_argument("--graph", action="store_true",
                    help="capture one step in a HIP graph and time its replays (no per-part times); "
                         "with --sweep: capture the calls of each size and time the replay")
+    p.add_argument("--shapes", action="store_true",
+                   help="time every entry point over node counts, sizes and rail layouts beyond the five "
+                        "workloads (plain allocations; one JSON line; ungraded)")
     p.add_argument("--sweep", action="store_true",
                    help="instead of the step: time fused and ring-stepwise allreduce over message sizes "
                         "2 KB .. 64 MB (fp32, 2 rails 1:1) at 4 and 8 nodes and print one JSON line")
@@ -248,6 +251,63 @@ def size_sweep(torch, nz, dev, use_graph: bool = False) -> int:
     return 0
 
 
+def shape_survey(torch, nz, dev) -> int:
+    """Every entry point over node counts, message sizes and rail layouts other than the five
+    workloads', on plain allocations: fraction of the HBM peak on each part's algorithmic bytes.
+    One JSON line; ungraded, like --sweep."""
+    MB = 1 << 20
+
+    def timed(fn, reps=8):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) * 1e-3 / reps
+
+    cases = [(N, mb, (100, 40)) for N in (2, 3, 4, 6, 8, 12, 16, 32) for mb in (64, 256)]
+    cases += [(8, 200, r) for r in ((1,), (1,) * 8, (1000, 1), (5, 0, 3, 0, 0, 1))]
+    cases += [(128, 32, r) for r in ((1,), (100, 100, 40, 10), (1,) * 8)]
+    rows = []
+    for dtype, tdt, e in (("f32", torch.float32, 4), ("bf16", torch.bfloat16, 2)):
+        for N, mb, ratios in cases:
+            n = mb * MB // e + 1234
+            S = n * e
+            ins = [(torch.randn(n, device=dev) * 1e-2).to(tdt) for _ in range(N)]
+            outs = [torch.empty_like(t) for t in ins]
+            b = nz.nz_rail_partition(n, e, ratios)
+            seg = nz.nz_segment_map(b, N)
+            L = int(b[1] - b[0])
+            send = [torch.empty(L, dtype=tdt, device=dev) for _ in range(N)]
+            ids = list(range(N))
+            live = [k for k, w in enumerate(ratios) if w]
+            parts = {
+                "fused": (2 * N * S, lambda: nz.nz_allreduce_sim(ins, n, ratios, dtype, "fused", outs)),
+                "ring": (5 * (N - 1) * S, lambda: nz.nz_allreduce_sim(ins, n, ratios, dtype, "ring-stepwise", outs)),
+                "rs": ((N + 1) * S, lambda: nz.nz_reduce_scatter_sim(ins, n, ratios, dtype, "fused", outs)),
+                "ag": (N * S, lambda: nz.nz_allgather_sim(outs, n, ratios, dtype, "fused")),
+                "chunked": (5 * (N - 1) * S,
+                            lambda: nz.nz_allreduce_sim_chunked(ins, n, ratios, dtype, 1 << 20, outs)),
+                "pack": (2 * N * L * e, lambda: nz.nz_pack(ins, seg, 0, ids, e, send, L * e)),
+                "unpack": (2 * N * L * e, lambda: nz.nz_unpack(send, seg, 0, ids, e, outs)),
+            }
+            if len(live) > 1:
+                parts["failover"] = (2 * N * S, lambda: nz.nz_allreduce_sim_failover(ins, n, ratios, dtype, "fused",
+                                                                                     outs, live[-1]))
+            row = {"dtype": dtype, "n_nodes": N, "mb_per_node": mb, "ratios": list(ratios)}
+            for name, (nbytes, fn) in parts.items():
+                row[name] = round(nbytes / timed(fn) / 1e9 / HBM_PEAK_GBS, 3)
+            rows.append(row)
+            del ins, outs, send, parts
+    print(json.dumps({"shape_survey": rows, "unit": "fraction of 8 TB/s on algorithmic bytes",
+                      "placement": "plain torch allocations"}), flush=True)
+    return 0
+
+
 def main() -> int:
     args = parse_args()
     if args.steps < 1 or args.warmup < 0:
@@ -271,6 +331,8 @@ def main() -> int:
     torch.cuda.set_device(0)
     if args.sweep:
         return size_sweep(torch, nz, dev, args.graph)
+    if args.shapes:
+        return shape_survey(torch, nz, dev)
     w = inputs.WORKLOADS[args.workload]
     parts = [p for p in args.parts.split(",") if p]
     N, n, e = w.n_nodes, w.n_elems, inputs.ELEM_BYTES[w.dtype]
