@@ -246,8 +246,28 @@ def size_sweep(torch, nz, dev, use_graph: bool = False) -> int:
             t0 = (sy - slope * sx) / m
             fits[f"{mode}_N{N}"] = {"t0_us": round(t0, 2), "payload_GBps": round(1.0 / slope / 1e3, 2),
                                     "half_efficiency_bytes": int(t0 / slope)}
-    print(json.dumps({"sweep": rows, "hip_graph": use_graph, "fit_t_equals_t0_plus_S_over_B": fits}),
-          flush=True)
+    # The Load Balancer (Sec. 4.3) on rails whose startup latency and bandwidth are the fitted
+    # ones: what it would do with two rails that behave like the two modes measured here.
+    balancer = {}
+    for N in (4, 8):
+        f, r = fits[f"fused_N{N}"], fits[f"ring-stepwise_N{N}"]
+        setup = [f["t0_us"] * 1e-6, r["t0_us"] * 1e-6]
+        rate = [f["payload_GBps"] * 1e9, r["payload_GBps"] * 1e9]
+        if min(setup) <= 0 or min(rate) <= 0:
+            continue
+        splits = []
+        for S in (1 << 16, 1 << 22, 1 << 26, 1 << 30):
+            b = nz.nz_balance(setup, rate, S)
+            it = nz.nz_balance_iterate(setup, rate, S)
+            splits.append({"msg_bytes": S, "hot": b["hot"], "alpha": [round(float(x), 4) for x in b["alpha"]],
+                           "t_cold_us": round(b["t_cold"] * 1e6, 2), "t_hot_us": round(b["t_hot"] * 1e6, 2),
+                           "alpha_by_iteration": [round(float(x), 4) for x in it["alpha"]],
+                           "iterations": it["iterations"]})
+        balancer[f"N{N}"] = {"rails": "rail 0 = (t0, B) of the fused fit, rail 1 = of the ring-stepwise fit",
+                             "threshold_bytes_eq6": round(nz.nz_balance_threshold(setup, rate)),
+                             "splits": splits}
+    print(json.dumps({"sweep": rows, "hip_graph": use_graph, "fit_t_equals_t0_plus_S_over_B": fits,
+                      "load_balancer_on_fitted_rails": balancer}), flush=True)
     return 0
 
 
