@@ -288,7 +288,10 @@ enum Collective { kAllreduce, kReduceScatter, kAllgather };
 
 // Bytes of one ring step up to which the step's output is kept in cache for
 // the next step to read (half of the 256 MB last-level cache).
-constexpr u64 kRingReuseBytes = 128ull << 20;
+#ifndef NZ_RING_REUSE_BYTES
+#define NZ_RING_REUSE_BYTES (128ull << 20)
+#endif
+constexpr u64 kRingReuseBytes = NZ_RING_REUSE_BYTES;
 
 // The launches of a ring: N - 1 reduce-scatter steps, then N - 1 allgather
 // steps (one half only for the phase collectives), each over whole segments.
