@@ -62,3 +62,43 @@ def test_graph_replays_match_eager(orc, dtype):
                 t.zero_()
             work()
             eager = snapshot()
+
+
+def test_graph_replays_of_the_multi_launch_forms(orc):
+    """The staged fused allreduce (three launches here), Ring_Chunked (a pipeline of launches) and
+    the two halves, captured together: replays equal the eager results."""
+    N, n, ratios, dtype = 8, 8 * (1 << 20) + 77, (100, 40), "f32"
+    assert nz.nz_allreduce_launches(N, n, ratios, dtype, "fused", N) == 3
+    ins = [inputs.node_buffer(dtype, n, 62, i, device=gu.DEV, std=1e-2) for i in range(N)]
+    fused = [torch.zeros_like(t) for t in ins]
+    chunked = [torch.zeros_like(t) for t in ins]
+    halves = [torch.zeros_like(t) for t in ins]
+
+    def work():
+        nz.nz_allreduce_sim(ins, n, ratios, dtype, "fused", fused)
+        nz.nz_allreduce_sim_chunked(ins, n, ratios, dtype, 1 << 18, chunked)
+        nz.nz_reduce_scatter_sim(ins, n, ratios, dtype, "fused", halves)
+        nz.nz_allgather_sim(halves, n, ratios, dtype, "fused")
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [t.clone() for t in fused + chunked + halves]
+
+    work()
+    eager = snapshot()
+    host = [inputs.to_host_storage(t) for t in ins]
+    gu.check_fused_against_oracle(orc, dtype, inputs.to_host_storage(fused[0]), host, "eager staged")
+    assert all(torch.equal(h, fused[0]) for h in halves)
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            work()
+    for replay in range(3):
+        for t in fused + chunked + halves:              # eager work between replays
+            t.fill_(float(replay + 1))
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for a, b in zip(eager, got):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), replay
