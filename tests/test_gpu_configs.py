@@ -9,6 +9,7 @@ import torch
 
 from paper_2405_17870_amd import inputs
 from paper_2405_17870_amd import nezha_sim as nz
+from paper_2405_17870_amd import placement
 
 import gpu_util as gu
 
@@ -128,3 +129,32 @@ def test_c5_128_nodes_full_compare(orc):
     gu.assert_same_bits(got, want[0], "f32", "c5 ring")
     assert all(np.array_equal(want[0], x) for x in want[1:8])
     gu.check_fused_against_oracle(orc, "f32", got, host, "c5 ring vs sum")
+
+
+@pytest.mark.parametrize("name", ["c2", "c3", "c5"])
+def test_fused_with_buffers_placed_as_the_benchmark_places_them(orc, name):
+    """With the benchmark's default placement (inputs in one region, outputs dealt out over all
+    three) the 8-node shapes run as one launch of the whole-message kernel, the 128-node one as
+    the pipeline: every sum against the oracle at full size, all outputs the same bits."""
+    w = inputs.WORKLOADS[name]
+    arena = placement.try_arena(gu.DEV)
+    if arena is None:
+        pytest.skip("not enough free HBM for a three-region arena")
+    _say(f"{name}: generating into placed buffers")
+    tdt = inputs.TORCH_DTYPE[w.dtype]
+    ins = [arena.alloc(w.n_elems, tdt, 0) for _ in range(w.n_nodes)]
+    for i, t in enumerate(ins):
+        t.copy_(inputs.node_buffer(w.dtype, w.n_elems, w.seed, i, device=gu.DEV, std=w.std,
+                                   outlier_frac=w.outlier_frac, outlier_scale=w.outlier_scale))
+    outs = arena.alloc_striped(w.n_nodes, w.n_elems, tdt)
+    for t in outs:
+        t.zero_()
+    e = inputs.ELEM_BYTES[w.dtype]
+    span = max(t.data_ptr() for t in outs) + w.n_elems * e - min(t.data_ptr() for t in outs)
+    launches = nz.nz_allreduce_launches(w.n_nodes, w.n_elems, w.ratios, w.dtype, "fused", w.n_nodes, span)
+    assert (launches == 1) == (w.n_nodes <= 16)
+    nz.nz_allreduce_sim(ins, w.n_elems, w.ratios, w.dtype, "fused", outs)
+    torch.cuda.synchronize()
+    assert _all_equal(outs)
+    host = [inputs.to_host_storage(t) for t in ins]
+    gu.check_fused_against_oracle(orc, w.dtype, inputs.to_host_storage(outs[w.n_nodes - 1]), host, name + " placed")
